@@ -1,0 +1,143 @@
+"""ctypes binding to the CPU oracle (oracle/signsgd_oracle.c).
+
+Test infrastructure only: tests, the smoke check and the benchmark's CPU
+baseline may import this; the product package must not.  All arrays are
+numpy, host memory.  Functions mutate m / x in place like the C routines and
+return the packed / voted words.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+F32 = 0
+BF16 = 1
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = ctypes.CDLL(path)
+        vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
+        L.sso_packed_words.restype = sz
+        L.sso_packed_words.argtypes = [sz]
+        L.sso_packed_bytes.restype = sz
+        L.sso_packed_bytes.argtypes = [sz]
+        L.sso_signum_pack.argtypes = [vp, i32, vp, f32, vp, sz]
+        L.sso_unpack.argtypes = [vp, sz, vp]
+        L.sso_vote_sum.argtypes = [vp, i32, sz, vp]
+        L.sso_majority_vote.argtypes = [vp, i32, vp, sz]
+        L.sso_sign_apply.argtypes = [vp, vp, f32, sz]
+        L.sso_signum_vote_step.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, sz]
+        L.sso_signum_vote_step_mt.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, sz, i32]
+        _lib = L
+    return _lib
+
+
+def packed_words(d):
+    return lib().sso_packed_words(d)
+
+
+def packed_bytes(d):
+    return lib().sso_packed_bytes(d)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError("%s failed with status %d" % (what, rc))
+
+
+def _ptr(a):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _ptr_array(arrs):
+    return (ctypes.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+
+
+def _grad_dtype(g):
+    if g.dtype == np.float32:
+        return F32
+    if g.dtype == np.uint16:          # bf16 bit patterns
+        return BF16
+    raise TypeError("gradient must be float32 or uint16 (bf16 bits), got %s" % g.dtype)
+
+
+def _need(a, dtype, n, name):
+    if a.dtype != dtype or not a.flags.c_contiguous or a.ndim != 1 or a.shape[0] < n:
+        raise TypeError("%s must be a contiguous 1-d %s array with >= %d elements" % (name, dtype, n))
+
+
+def new_bits(d):
+    return np.empty(packed_bytes(d) // 4, dtype=np.uint32)
+
+
+def signum_pack(g, m, beta, d=None):
+    d = len(g) if d is None else d
+    gdt = _grad_dtype(g)
+    _need(g, g.dtype, d, "g")
+    if m is not None:
+        _need(m, np.float32, d, "m")
+    packed = new_bits(d)
+    _check(lib().sso_signum_pack(_ptr(g), gdt, _ptr(m) if m is not None else None,
+                                 float(np.float32(beta)), _ptr(packed), d), "sso_signum_pack")
+    return packed
+
+
+def unpack(bits, d):
+    _need(bits, np.uint32, packed_words(d), "bits")
+    out = np.empty(d, dtype=np.int8)
+    _check(lib().sso_unpack(_ptr(bits), d, _ptr(out)), "sso_unpack")
+    return out
+
+
+def vote_sum(packed, d):
+    for p in packed:
+        _need(p, np.uint32, packed_words(d), "packed")
+    out = np.empty(d, dtype=np.int32)
+    _check(lib().sso_vote_sum(_ptr_array(packed), len(packed), d, _ptr(out)), "sso_vote_sum")
+    return out
+
+
+def majority_vote(packed, d):
+    for p in packed:
+        _need(p, np.uint32, packed_words(d), "packed")
+    voted = new_bits(d)
+    _check(lib().sso_majority_vote(_ptr_array(packed), len(packed), _ptr(voted), d),
+           "sso_majority_vote")
+    return voted
+
+
+def sign_apply(x, bits, delta, d=None):
+    d = len(x) if d is None else d
+    _need(x, np.float32, d, "x")
+    _need(bits, np.uint32, packed_words(d), "bits")
+    _check(lib().sso_sign_apply(_ptr(x), _ptr(bits), float(np.float32(delta)), d), "sso_sign_apply")
+
+
+def signum_vote_step(g, m, beta, delta, x, d=None, want_packed=False, threads=1):
+    """g: list of M gradient arrays; m: list of M momentum arrays or None."""
+    M = len(g)
+    d = len(x) if d is None else d
+    gdt = _grad_dtype(g[0])
+    for a in g:
+        _need(a, g[0].dtype, d, "g")
+    if m is not None:
+        for a in m:
+            _need(a, np.float32, d, "m")
+    _need(x, np.float32, d, "x")
+    voted = new_bits(d)
+    packed = [new_bits(d) for _ in range(M)] if want_packed else None
+    args = [_ptr_array(g), gdt, _ptr_array(m) if m is not None else None, M,
+            float(np.float32(beta)), float(np.float32(delta)), _ptr(x), _ptr(voted),
+            _ptr_array(packed) if packed is not None else None, d]
+    if threads == 1:
+        _check(lib().sso_signum_vote_step(*args), "sso_signum_vote_step")
+    else:
+        _check(lib().sso_signum_vote_step_mt(*args, int(threads)), "sso_signum_vote_step_mt")
+    return (voted, packed) if want_packed else voted

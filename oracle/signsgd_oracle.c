@@ -1,0 +1,254 @@
+/*
+ * CPU oracle for the signSGD / Signum + majority-vote step.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It exists so that the HIP
+ * library can be checked bit for bit against something a reader can verify
+ * against the paper by eye.  Only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg may call it.  It shares no code with the HIP
+ * path and is deliberately plain: one scalar loop per definition, no
+ * blocking, no bit tricks, no vector intrinsics.
+ *
+ * What each routine follows (arxiv 1802.04434):
+ *   sso_signum_pack   Algorithm 2 (Signum), momentum line and the sign that
+ *                     the next line takes; with m == NULL, Algorithm 1's
+ *                     sign(g).  One bit per coordinate as in Table 1.
+ *   sso_majority_vote Algorithm 3, server side: sign[ sum_m sign(g_m) ]
+ *                     (the "(best)" update of Section 4).
+ *   sso_sign_apply    Algorithm 1 / Algorithm 3, worker side:
+ *                     x <- x - delta * sign(...).
+ *   sso_signum_vote_step  the three above in sequence over M workers.
+ *   sso_vote_sum      the integer sum_m sign(g_m) of Section 4's "(good)".
+ *
+ * Readings the paper leaves open, fixed here:
+ *   sign(v) = -1 if v < 0, else +1.  Zero (either sign of zero) is "+".
+ *     The same rule is applied to the integer vote sum, so an even-M tie
+ *     votes "+".  (One bit in each direction leaves no code for 0, and the
+ *     analysis of Theorem 1 moves every coordinate by exactly delta.)
+ *   bit = 1 means sign = -1; coordinate i is bit (i mod 32), least
+ *     significant first, of 32-bit word (i div 32); unused bits are 0, and
+ *     zero words are appended until the byte length is a multiple of 16.
+ *   momentum is fp32: fl(fl(beta*m) + fl((1-beta)*g)), (1-beta) rounded once,
+ *     no fused multiply-add (build with -ffp-contract=off), subnormals kept.
+ *   with momentum and M workers, every worker keeps its own m and votes
+ *     with sign(m_m).
+ *   bf16 gradients are widened to fp32 exactly before use.
+ *
+ * Parity pins: tests/test_oracle_*.py (brute force on small sizes, exact
+ * rational rounding, closed forms and invariants).
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define SSO_OK 0
+#define SSO_ERR_NULL (-1)
+#define SSO_ERR_BAD_M (-2)
+#define SSO_ERR_DTYPE (-4)
+#define SSO_ERR_ARG (-5)
+
+#define SSO_F32 0
+#define SSO_BF16 1
+
+size_t sso_packed_words(size_t d) { return d / 32 + (d % 32 != 0); }
+
+size_t sso_packed_bytes(size_t d)
+{
+    size_t bytes = 4 * sso_packed_words(d);
+    while (bytes % 16 != 0) bytes += 4;
+    return bytes;
+}
+
+/* gradient element i as an fp32 value */
+static float grad_at(const void *g, int gdt, size_t i)
+{
+    if (gdt == SSO_F32) return ((const float *)g)[i];
+    /* bf16 is the upper half of an fp32 */
+    uint32_t bits = (uint32_t)((const uint16_t *)g)[i] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return f;
+}
+
+static int bit_at(const uint32_t *bits, size_t i)
+{
+    return (int)((bits[i / 32] >> (i % 32)) & 1u);
+}
+
+static void set_bit(uint32_t *bits, size_t i)
+{
+    bits[i / 32] |= (uint32_t)1 << (i % 32);
+}
+
+/* Algorithm 2: m <- beta m + (1-beta) g ; bit_i <- [sign(m_i) = -1].
+ * m == NULL: Algorithm 1, bit_i <- [sign(g_i) = -1]. */
+int sso_signum_pack(const void *g, int gdt, float *m, float beta,
+                    uint32_t *packed, size_t d)
+{
+    if (gdt != SSO_F32 && gdt != SSO_BF16) return SSO_ERR_DTYPE;
+    if (d == 0) return SSO_OK;
+    if (!g || !packed) return SSO_ERR_NULL;
+    memset(packed, 0, sso_packed_bytes(d));
+    const float one_minus_beta = 1.0f - beta;
+    for (size_t i = 0; i < d; ++i) {
+        float gi = grad_at(g, gdt, i);
+        float v;
+        if (m) {
+            float t1 = beta * m[i];
+            float t2 = one_minus_beta * gi;
+            m[i] = t1 + t2;
+            v = m[i];
+        } else {
+            v = gi;
+        }
+        if (v < 0.0f) set_bit(packed, i);
+    }
+    return SSO_OK;
+}
+
+/* the +-1 value a packed bit stands for */
+int sso_unpack(const uint32_t *bits, size_t d, int8_t *out)
+{
+    if (d == 0) return SSO_OK;
+    if (!bits || !out) return SSO_ERR_NULL;
+    for (size_t i = 0; i < d; ++i) out[i] = bit_at(bits, i) ? -1 : +1;
+    return SSO_OK;
+}
+
+/* Section 4 "(good)": out_i = sum_m sign_m,i */
+int sso_vote_sum(const uint32_t *const *packed, int M, size_t d, int32_t *out)
+{
+    if (M < 1) return SSO_ERR_BAD_M;
+    if (d == 0) return SSO_OK;
+    if (!packed || !out) return SSO_ERR_NULL;
+    for (int w = 0; w < M; ++w)
+        if (!packed[w]) return SSO_ERR_NULL;
+    for (size_t i = 0; i < d; ++i) {
+        int32_t s = 0;
+        for (int w = 0; w < M; ++w) s += bit_at(packed[w], i) ? -1 : +1;
+        out[i] = s;
+    }
+    return SSO_OK;
+}
+
+/* Algorithm 3, server: voted bit_i <- [ sign( sum_m sign_m,i ) = -1 ] */
+int sso_majority_vote(const uint32_t *const *packed, int M, uint32_t *voted,
+                      size_t d)
+{
+    if (M < 1) return SSO_ERR_BAD_M;
+    if (d == 0) return SSO_OK;
+    if (!packed || !voted) return SSO_ERR_NULL;
+    for (int w = 0; w < M; ++w)
+        if (!packed[w]) return SSO_ERR_NULL;
+    memset(voted, 0, sso_packed_bytes(d));
+    for (size_t i = 0; i < d; ++i) {
+        int sum = 0;
+        for (int w = 0; w < M; ++w) sum += bit_at(packed[w], i) ? -1 : +1;
+        if (sum < 0) set_bit(voted, i);
+    }
+    return SSO_OK;
+}
+
+/* Algorithm 1 / Algorithm 3, worker: x_i <- x_i - delta * s_i, s_i = +-1 */
+int sso_sign_apply(float *x, const uint32_t *bits, float delta, size_t d)
+{
+    if (d == 0) return SSO_OK;
+    if (!x || !bits) return SSO_ERR_NULL;
+    for (size_t i = 0; i < d; ++i) {
+        if (bit_at(bits, i))
+            x[i] = x[i] + delta; /* s = -1 */
+        else
+            x[i] = x[i] - delta; /* s = +1 */
+    }
+    return SSO_OK;
+}
+
+/* One whole step over M workers: Algorithm 2 on every worker, then
+ * Algorithm 3.  g, m: arrays of M host pointers (m == NULL: no momentum).
+ * packed_out: NULL, or M buffers that receive every worker's sign bits. */
+int sso_signum_vote_step(const void *const *g, int gdt, float *const *m, int M,
+                         float beta, float delta, float *x, uint32_t *voted,
+                         uint32_t *const *packed_out, size_t d)
+{
+    if (M < 1) return SSO_ERR_BAD_M;
+    if (gdt != SSO_F32 && gdt != SSO_BF16) return SSO_ERR_DTYPE;
+    if (d == 0) return SSO_OK;
+    if (!g || !x || !voted) return SSO_ERR_NULL;
+
+    size_t bytes = sso_packed_bytes(d);
+    uint32_t **signs = malloc((size_t)M * sizeof *signs);
+    uint32_t *own = NULL;
+    if (!signs) return SSO_ERR_ARG;
+    if (!packed_out) {
+        own = malloc((size_t)M * bytes);
+        if (!own) {
+            free(signs);
+            return SSO_ERR_ARG;
+        }
+    }
+    int rc = SSO_OK;
+    for (int w = 0; w < M && rc == SSO_OK; ++w) {
+        signs[w] = packed_out ? packed_out[w] : own + (size_t)w * (bytes / 4);
+        rc = sso_signum_pack(g[w], gdt, m ? m[w] : NULL, beta, signs[w], d);
+    }
+    if (rc == SSO_OK)
+        rc = sso_majority_vote((const uint32_t *const *)signs, M, voted, d);
+    if (rc == SSO_OK) rc = sso_sign_apply(x, voted, delta, d);
+    free(own);
+    free(signs);
+    return rc;
+}
+
+/* The same step with the coordinate range cut into `nthreads` contiguous
+ * pieces whose boundaries are multiples of 32 (whole packed words), each
+ * piece handed to sso_signum_vote_step on its own thread.  Coordinates do
+ * not interact, so this is the same result; it only exists so that the
+ * benchmark can time the oracle on all host cores as well as on one. */
+int sso_signum_vote_step_mt(const void *const *g, int gdt, float *const *m,
+                            int M, float beta, float delta, float *x,
+                            uint32_t *voted, uint32_t *const *packed_out,
+                            size_t d, int nthreads)
+{
+    if (nthreads < 1) return SSO_ERR_ARG;
+    if (M < 1) return SSO_ERR_BAD_M;
+    if (gdt != SSO_F32 && gdt != SSO_BF16) return SSO_ERR_DTYPE;
+    if (d == 0) return SSO_OK;
+    if (!g || !x || !voted) return SSO_ERR_NULL;
+
+    /* piece length: multiple of 128 coordinates, so that every piece's
+     * packed range starts on a 16-byte boundary and pad words of one piece
+     * never land in the next */
+    size_t per = (d + (size_t)nthreads - 1) / (size_t)nthreads;
+    per = (per + 127) / 128 * 128;
+    int pieces = (int)((d + per - 1) / per);
+    size_t gsize = gdt == SSO_F32 ? 4 : 2;
+    int rc_all = SSO_OK;
+
+#pragma omp parallel for num_threads(nthreads) schedule(static, 1)
+    for (int p = 0; p < pieces; ++p) {
+        size_t lo = (size_t)p * per;
+        size_t n = d - lo < per ? d - lo : per;
+        const void **gp = malloc((size_t)M * sizeof *gp);
+        float **mp = malloc((size_t)M * sizeof *mp);
+        uint32_t **pp = malloc((size_t)M * sizeof *pp);
+        int rc = SSO_ERR_ARG;
+        if (gp && mp && pp) {
+            for (int w = 0; w < M; ++w) {
+                gp[w] = (const char *)g[w] + lo * gsize;
+                mp[w] = m ? m[w] + lo : NULL;
+                pp[w] = packed_out ? packed_out[w] + lo / 32 : NULL;
+            }
+            rc = sso_signum_vote_step(gp, gdt, m ? mp : NULL, M, beta, delta,
+                                      x + lo, voted + lo / 32,
+                                      packed_out ? pp : NULL, n);
+        }
+        free(gp);
+        free(mp);
+        free(pp);
+        if (rc != SSO_OK) {
+#pragma omp critical
+            rc_all = rc;
+        }
+    }
+    return rc_all;
+}
