@@ -1,0 +1,140 @@
+/*
+ * signsgd.h - C ABI of the MI355X (gfx950) library for the per-step hot path
+ * of signSGD / Signum with majority vote (arxiv 1802.04434, Algorithms 1-3).
+ *
+ * One step over a d-coordinate model held by M data-parallel workers:
+ *
+ *   m_w <- beta m_w + (1-beta) g_w          Algorithm 2 (Signum), per worker
+ *   s_w  = sign(m_w)   (sign(g_w) without momentum: Algorithm 1)
+ *   one bit per coordinate per worker       Table 1: 1 bit up, 1 bit down
+ *   v    = sign( sum_w s_w )                Algorithm 3, server ("(best)", Section 4)
+ *   x   <- x - delta v                      Algorithm 3, worker
+ *
+ * On one GPU the M workers are M device buffers.
+ *
+ * CONVENTIONS (the paper leaves these open; they are part of this ABI)
+ *   sign(v)    -1 if v < 0, otherwise +1.  +0.0 and -0.0 are "+".  The same
+ *              rule is applied to the integer vote sum: an even-M tie is "+".
+ *   bits       bit = 1 means sign = -1.  Coordinate i is bit (i mod 32),
+ *              least significant first, of the uint32 word (i div 32).  A
+ *              packed buffer holds ss_packed_bytes(d) bytes: ceil(d/32) words
+ *              rounded up to a multiple of 16 bytes.  Every routine that
+ *              writes a packed buffer writes ALL of those bytes; bits at and
+ *              beyond coordinate d are written as 0.
+ *   arithmetic fp32, round to nearest even, subnormals kept, no fused
+ *              multiply-add:  m <- fl( fl(beta*m) + fl(omb*g) ) with
+ *              omb = fl(1 - beta) computed once;  x <- fl(x - delta) or
+ *              fl(x + delta).  bf16 gradients are widened to fp32 exactly.
+ *              NaN / Inf inputs follow these rules literally (a NaN is not
+ *              < 0, hence "+"); they are not an error.
+ *   momentum   with M > 1 every worker owns its momentum buffer and votes
+ *              with sign(m_w).
+ *
+ * MEMORY      Every data pointer (g, m, x, packed, voted) is DEVICE memory,
+ *             owned by the caller, 16-byte aligned, and no two buffers of one
+ *             call may overlap.  Arrays OF pointers (g[], m[], packed[]) are
+ *             HOST arrays of M device pointers; they are copied into the
+ *             kernel arguments during the call and may be freed on return.
+ *             The library allocates nothing and keeps no state between calls.
+ * STREAMS     hip_stream is a hipStream_t passed as void* (NULL: the default
+ *             stream).  Work is enqueued and the call returns without
+ *             synchronising.  Calls are thread safe.
+ * ERRORS      Every call returns SS_OK or a negative ss_status and never
+ *             aborts.  Arguments are validated before anything is enqueued:
+ *             on an argument error nothing has been launched.  d == 0 is
+ *             SS_OK and launches nothing.
+ */
+#ifndef SIGNSGD_H
+#define SIGNSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SS_OK = 0,
+    SS_ERR_NULL = -1,  /* a required pointer (or an entry of a pointer array) is NULL */
+    SS_ERR_BAD_M = -2, /* M < 1 or M > SS_MAX_WORKERS */
+    SS_ERR_ALIGN = -3, /* a data pointer is not 16-byte aligned */
+    SS_ERR_DTYPE = -4, /* unknown gradient dtype */
+    SS_ERR_ARG = -5,   /* any other invalid argument (e.g. d too large) */
+    SS_ERR_HIP = -6    /* the HIP runtime refused the launch; see ss_last_hip_error */
+} ss_status;
+
+/* gradient element type; momentum and parameters are always fp32 */
+typedef enum { SS_F32 = 0, SS_BF16 = 1 } ss_dtype;
+
+#define SS_MAX_WORKERS 64
+
+/* ceil(d/32): words that carry payload bits */
+size_t ss_packed_words(size_t d);
+/* bytes a packed / voted buffer for d coordinates must hold (multiple of 16) */
+size_t ss_packed_bytes(size_t d);
+
+/*
+ * One worker's half of a step.  Algorithm 2: m <- beta m + (1-beta) g, then
+ * packed <- bits of sign(m).  With m == NULL, Algorithm 1: packed <- bits of
+ * sign(g), beta ignored.
+ *   g       in   d elements of type gdt
+ *   m       i/o  d x fp32, or NULL
+ *   packed  out  ss_packed_bytes(d) bytes
+ */
+int ss_signum_pack(const void *g, ss_dtype gdt, float *m, float beta,
+                   uint32_t *packed, size_t d, void *hip_stream);
+
+/*
+ * Algorithm 3, server side: voted <- bits of sign( sum_w sign_w ), where
+ * packed[w] holds worker w's sign bits.  "-" wins at a coordinate iff more
+ * than M/2 workers are "-".
+ *   packed  in   host array of M device pointers, ss_packed_bytes(d) bytes each
+ *   voted   out  ss_packed_bytes(d) bytes
+ */
+int ss_majority_vote(const uint32_t *const *packed, int M, uint32_t *voted,
+                     size_t d, void *hip_stream);
+
+/*
+ * Algorithm 1 / Algorithm 3, worker side: x_i <- x_i - delta * s_i with
+ * s_i = -1 where bit i of `bits` is set, +1 otherwise.  `bits` is a voted
+ * buffer, or a single worker's packed buffer.
+ *   x     i/o  d x fp32
+ *   bits  in   ss_packed_bytes(d) bytes (only the first ceil(d/32) words are read)
+ */
+int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d,
+                  void *hip_stream);
+
+/*
+ * The whole step in one pass over memory: for every worker the momentum
+ * update and sign (Algorithm 2), the vote and the parameter update
+ * (Algorithm 3).  Identical results, bit for bit, to M calls of
+ * ss_signum_pack, one ss_majority_vote and one ss_sign_apply.
+ *   g           in   host array of M device pointers, d elements of gdt each
+ *   m           i/o  host array of M device pointers, d x fp32 each; NULL = no
+ *                    momentum (Algorithm 1 + 3: vote on sign(g_w), beta ignored)
+ *   x           i/o  d x fp32
+ *   voted       out  ss_packed_bytes(d) bytes: the bits that were applied
+ *   packed_out  out  NULL, or host array of M device pointers that receive
+ *                    every worker's sign bits (ss_packed_bytes(d) bytes each)
+ */
+int ss_signum_vote_step(const void *const *g, ss_dtype gdt, float *const *m,
+                        int M, float beta, float delta, float *x,
+                        uint32_t *voted, uint32_t *const *packed_out, size_t d,
+                        void *hip_stream);
+
+/* the hipError_t (as int) behind this thread's most recent SS_ERR_HIP; 0 if none */
+int ss_last_hip_error(void);
+
+/*
+ * Measurement aid, not part of the method: dst <- src, nbytes (multiple of 16,
+ * both 16-byte aligned, device memory), with the same 128-bit streaming
+ * accesses the step kernels use.  Gives the copy bandwidth of the machine and
+ * a known byte count against which hardware traffic counters are scaled.
+ */
+int ss_stream_copy(void *dst, const void *src, size_t nbytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIGNSGD_H */

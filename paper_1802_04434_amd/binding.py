@@ -1,0 +1,171 @@
+"""ctypes marshalling for libsignsgd.so.  Function names and argument order
+follow include/signsgd.h (ss_ prefix dropped)."""
+import ctypes
+import os
+
+import torch
+
+F32 = 0
+BF16 = 1
+MAX_WORKERS = 64
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsignsgd.so")
+_lib = None
+
+_STATUS = {0: "SS_OK", -1: "SS_ERR_NULL", -2: "SS_ERR_BAD_M", -3: "SS_ERR_ALIGN",
+           -4: "SS_ERR_DTYPE", -5: "SS_ERR_ARG", -6: "SS_ERR_HIP"}
+
+
+class SignSGDError(RuntimeError):
+    def __init__(self, call, status):
+        self.status = status
+        detail = ""
+        if status == -6 and _lib is not None:
+            detail = " (hipError_t %d)" % _lib.ss_last_hip_error()
+        super().__init__("%s returned %s%s" % (call, _STATUS.get(status, status), detail))
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_1802_04434_amd.build` "
+                "(there is no fallback path)" % _LIB_PATH)
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, sz, i32, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_float
+        L.ss_packed_words.restype = sz
+        L.ss_packed_words.argtypes = [sz]
+        L.ss_packed_bytes.restype = sz
+        L.ss_packed_bytes.argtypes = [sz]
+        L.ss_last_hip_error.restype = i32
+        L.ss_last_hip_error.argtypes = []
+        L.ss_signum_pack.argtypes = [vp, i32, vp, f32, vp, sz, vp]
+        L.ss_majority_vote.argtypes = [vp, i32, vp, sz, vp]
+        L.ss_sign_apply.argtypes = [vp, vp, f32, sz, vp]
+        L.ss_signum_vote_step.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, sz, vp]
+        L.ss_stream_copy.argtypes = [vp, vp, sz, vp]
+        for name in ("ss_signum_pack", "ss_majority_vote", "ss_sign_apply", "ss_signum_vote_step",
+                     "ss_stream_copy"):
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def packed_words(d):
+    return load_library().ss_packed_words(d)
+
+
+def packed_bytes(d):
+    return load_library().ss_packed_bytes(d)
+
+
+def last_hip_error():
+    return load_library().ss_last_hip_error()
+
+
+def new_bits(d, device="cuda"):
+    """uninitialised packed / voted buffer for d coordinates (int32 storage)"""
+    return torch.empty(packed_bytes(d) // 4, dtype=torch.int32, device=device)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev(t, dtype, n, name):
+    if not t.is_cuda:
+        raise TypeError("%s must live in device memory" % name)
+    if t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise TypeError("%s has dtype %s" % (name, t.dtype))
+    if not t.is_contiguous() or t.numel() < n:
+        raise TypeError("%s must be contiguous with at least %d elements" % (name, n))
+    return t.data_ptr()
+
+
+def _grad_dtype(g):
+    if g.dtype == torch.float32:
+        return F32
+    if g.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("gradient dtype must be float32 or bfloat16, got %s" % g.dtype)
+
+
+def _ptr_array(ptrs):
+    return (ctypes.c_void_p * len(ptrs))(*ptrs)
+
+
+def _check(call, status):
+    if status != 0:
+        raise SignSGDError(call, status)
+
+
+_BITS = (torch.int32, torch.uint32) if hasattr(torch, "uint32") else (torch.int32,)
+
+
+def signum_pack(g, m, beta, packed, d=None, stream=None):
+    """ss_signum_pack: m <- beta m + (1-beta) g; packed <- bits of sign(m)
+    (m None: bits of sign(g))."""
+    L = load_library()
+    d = g.numel() if d is None else d
+    gp = _dev(g, (torch.float32, torch.bfloat16), d, "g")
+    mp = _dev(m, torch.float32, d, "m") if m is not None else None
+    pp = _dev(packed, _BITS, L.ss_packed_bytes(d) // 4, "packed")
+    _check("ss_signum_pack", L.ss_signum_pack(gp, _grad_dtype(g), mp, beta, pp, d, _stream(stream)))
+    return packed
+
+
+def majority_vote(packed, voted, d, stream=None):
+    """ss_majority_vote: voted <- bits of sign(sum_w sign_w)"""
+    L = load_library()
+    n = L.ss_packed_bytes(d) // 4
+    ptrs = [_dev(p, _BITS, n, "packed[%d]" % i) for i, p in enumerate(packed)]
+    vp = _dev(voted, _BITS, n, "voted")
+    _check("ss_majority_vote", L.ss_majority_vote(_ptr_array(ptrs), len(ptrs), vp, d, _stream(stream)))
+    return voted
+
+
+def sign_apply(x, bits, delta, d=None, stream=None):
+    """ss_sign_apply: x <- x - delta * (+-1 from bits)"""
+    L = load_library()
+    d = x.numel() if d is None else d
+    xp = _dev(x, torch.float32, d, "x")
+    bp = _dev(bits, _BITS, L.ss_packed_words(d), "bits")
+    _check("ss_sign_apply", L.ss_sign_apply(xp, bp, delta, d, _stream(stream)))
+    return x
+
+
+def signum_vote_step(g, m, beta, delta, x, voted, packed_out=None, d=None, stream=None):
+    """ss_signum_vote_step: the whole step for M = len(g) workers in one pass.
+    g: list of gradients; m: list of momentum buffers or None."""
+    L = load_library()
+    M = len(g)
+    d = x.numel() if d is None else d
+    n = L.ss_packed_bytes(d) // 4
+    gdt = _grad_dtype(g[0])
+    gp = [_dev(t, g[0].dtype, d, "g[%d]" % i) for i, t in enumerate(g)]
+    mp = [_dev(t, torch.float32, d, "m[%d]" % i) for i, t in enumerate(m)] if m is not None else None
+    pp = [_dev(t, _BITS, n, "packed_out[%d]" % i) for i, t in enumerate(packed_out)] \
+        if packed_out is not None else None
+    if (mp is not None and len(mp) != M) or (pp is not None and len(pp) != M):
+        raise ValueError("g, m and packed_out must have one entry per worker")
+    xp = _dev(x, torch.float32, d, "x")
+    vp = _dev(voted, _BITS, n, "voted")
+    _check("ss_signum_vote_step", L.ss_signum_vote_step(
+        _ptr_array(gp), gdt, _ptr_array(mp) if mp is not None else None, M, beta, delta, xp, vp,
+        _ptr_array(pp) if pp is not None else None, d, _stream(stream)))
+    return voted
+
+
+def stream_copy(dst, src, nbytes, stream=None):
+    """ss_stream_copy: measurement aid, dst <- src"""
+    L = load_library()
+    _check("ss_stream_copy", L.ss_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)))

@@ -1,0 +1,268 @@
+// C ABI of the library (see include/signsgd.h): argument validation, kernel
+// selection and launch.  Nothing here allocates or synchronises.
+#include "../../include/signsgd.h"
+
+#include <hip/hip_runtime.h>
+
+#include "step_kernels.hpp"
+#include "vote_apply_kernels.hpp"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+constexpr size_t kMaxGrid = 0x7FFFFFFFull;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int launch_status() {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return SS_ERR_HIP;
+    }
+    return SS_OK;
+}
+
+// how the coordinate range is cut for a kernel that handles R rows per block
+struct Tiling {
+    size_t n_tiles;      // blocks on the vector path
+    size_t tail_blocks;  // blocks of 256 scalar coordinates, zero padding included
+    size_t words_total;
+};
+
+inline Tiling make_tiling(size_t d, int rows, bool covers_padding) {
+    Tiling t;
+    t.words_total = ss_packed_bytes(d) / 4;
+    t.n_tiles = d / ((size_t)rows * ss::kRowCoords);
+    const size_t done = t.n_tiles * (size_t)rows * ss::kRowCoords;
+    const size_t end = covers_padding ? t.words_total * 32 : d;
+    t.tail_blocks = (end - done + ss::kBlock - 1) / ss::kBlock;
+    return t;
+}
+
+// ------------------------------------------------------------------------
+// Launch shapes.  R = rows of 1024 coordinates per block, BW = workers whose
+// loads are in flight together.  A lane keeps 2*BW*R (momentum) or BW*R
+// (no momentum) 128-bit loads in flight, plus R for x.
+#ifdef SS_FORCE_ROWS
+constexpr int rows_for(int, bool) { return SS_FORCE_ROWS; }
+#else
+constexpr int rows_for(int m, bool has_m) {
+    const int streams = m * (has_m ? 2 : 1);
+    return streams >= 8 ? 1 : streams >= 4 ? 2 : 4;
+}
+#endif
+#ifdef SS_FORCE_BATCH
+constexpr int batch_for(int m) { return m < SS_FORCE_BATCH ? m : SS_FORCE_BATCH; }
+#else
+constexpr int batch_for(int m) { return m < 8 ? m : 8; }
+#endif
+
+template <int MT, bool HAS_M, bool VOTE, typename G>
+int launch_step_fixed(const void *const *g, float *const *m, uint32_t *const *packed, float beta,
+                      float delta, float *x, uint32_t *voted, size_t d, hipStream_t stream) {
+    constexpr int R = rows_for(MT, HAS_M);
+    constexpr int BW = batch_for(MT);
+    ss::StepArgs<MT> a;
+    for (int w = 0; w < MT; ++w) {
+        a.p.g[w] = g[w];
+        a.p.m[w] = HAS_M ? m[w] : nullptr;
+        a.p.packed[w] = packed ? packed[w] : nullptr;
+    }
+    const Tiling t = make_tiling(d, R, true);
+    a.x = x;
+    a.voted = voted;
+    a.beta = beta;
+    a.omb = 1.0f - beta;
+    a.delta = delta;
+    a.M = MT;
+    a.write_packed = packed != nullptr;
+    a.d = d;
+    a.n_tiles = t.n_tiles;
+    a.words_total = t.words_total;
+    const size_t grid = t.n_tiles + t.tail_blocks;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::step_kernel<MT, MT, BW, R, HAS_M, VOTE, G><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    return launch_status();
+}
+
+template <bool HAS_M, typename G>
+int launch_step_any(int M, const void *const *g, float *const *m, uint32_t *const *packed, float beta,
+                    float delta, float *x, uint32_t *voted, size_t d, hipStream_t stream) {
+    constexpr int R = 1;
+    constexpr int BW = 8;
+    ss::StepArgs<SS_MAX_WORKERS> a;
+    for (int w = 0; w < SS_MAX_WORKERS; ++w) {
+        a.p.g[w] = w < M ? g[w] : nullptr;
+        a.p.m[w] = (HAS_M && w < M) ? m[w] : nullptr;
+        a.p.packed[w] = (packed && w < M) ? packed[w] : nullptr;
+    }
+    const Tiling t = make_tiling(d, R, true);
+    a.x = x;
+    a.voted = voted;
+    a.beta = beta;
+    a.omb = 1.0f - beta;
+    a.delta = delta;
+    a.M = M;
+    a.write_packed = packed != nullptr;
+    a.d = d;
+    a.n_tiles = t.n_tiles;
+    a.words_total = t.words_total;
+    const size_t grid = t.n_tiles + t.tail_blocks;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::step_kernel<0, SS_MAX_WORKERS, BW, R, HAS_M, true, G>
+        <<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    return launch_status();
+}
+
+template <bool HAS_M, typename G>
+int launch_step(int M, const void *const *g, float *const *m, uint32_t *const *packed, float beta,
+                float delta, float *x, uint32_t *voted, size_t d, hipStream_t stream) {
+#define SS_CASE(n) \
+    case n: return launch_step_fixed<n, HAS_M, true, G>(g, m, packed, beta, delta, x, voted, d, stream)
+    switch (M) {
+        SS_CASE(1); SS_CASE(2); SS_CASE(3); SS_CASE(4); SS_CASE(5); SS_CASE(6); SS_CASE(7); SS_CASE(8);
+        SS_CASE(16);
+        default: return launch_step_any<HAS_M, G>(M, g, m, packed, beta, delta, x, voted, d, stream);
+    }
+#undef SS_CASE
+}
+
+template <int M>
+int launch_vote_fixed(const uint32_t *const *packed, uint32_t *voted, size_t d, hipStream_t stream) {
+    ss::VoteArgs<M> a;
+    for (int w = 0; w < M; ++w) a.packed[w] = packed[w];
+    a.voted = voted;
+    a.M = M;
+    a.d = d;
+    a.n_vec = ss_packed_bytes(d) / 16;
+    const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::vote_kernel<M><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    return launch_status();
+}
+
+int launch_vote_any(const uint32_t *const *packed, int M, uint32_t *voted, size_t d, hipStream_t stream) {
+    ss::VoteArgs<SS_MAX_WORKERS> a;
+    for (int w = 0; w < SS_MAX_WORKERS; ++w) a.packed[w] = w < M ? packed[w] : nullptr;
+    a.voted = voted;
+    a.M = M;
+    a.d = d;
+    a.n_vec = ss_packed_bytes(d) / 16;
+    const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::vote_kernel_any<<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    return launch_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ss_packed_words(size_t d) { return d / 32 + (d % 32 != 0 ? 1 : 0); }
+
+size_t ss_packed_bytes(size_t d) { return (ss_packed_words(d) * 4 + 15) / 16 * 16; }
+
+int ss_last_hip_error(void) { return g_last_hip_error; }
+
+int ss_signum_pack(const void *g, ss_dtype gdt, float *m, float beta, uint32_t *packed, size_t d,
+                   void *hip_stream) {
+    if (gdt != SS_F32 && gdt != SS_BF16) return SS_ERR_DTYPE;
+    if (d == 0) return SS_OK;
+    if (!g || !packed) return SS_ERR_NULL;
+    if (!aligned16(g) || !aligned16(m) || !aligned16(packed)) return SS_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const void *gs[1] = {g};
+    float *ms[1] = {m};
+    uint32_t *ps[1] = {packed};
+    if (m) {
+        if (gdt == SS_F32)
+            return launch_step_fixed<1, true, false, ss::F32Grad>(gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+        return launch_step_fixed<1, true, false, ss::Bf16Grad>(gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+    }
+    if (gdt == SS_F32)
+        return launch_step_fixed<1, false, false, ss::F32Grad>(gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+    return launch_step_fixed<1, false, false, ss::Bf16Grad>(gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+}
+
+int ss_majority_vote(const uint32_t *const *packed, int M, uint32_t *voted, size_t d, void *hip_stream) {
+    if (M < 1 || M > SS_MAX_WORKERS) return SS_ERR_BAD_M;
+    if (d == 0) return SS_OK;
+    if (!packed || !voted) return SS_ERR_NULL;
+    for (int w = 0; w < M; ++w)
+        if (!packed[w]) return SS_ERR_NULL;
+    if (!aligned16(voted)) return SS_ERR_ALIGN;
+    for (int w = 0; w < M; ++w)
+        if (!aligned16(packed[w])) return SS_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+#define SS_CASE(n) \
+    case n: return launch_vote_fixed<n>(packed, voted, d, stream)
+    switch (M) {
+        SS_CASE(1); SS_CASE(2); SS_CASE(3); SS_CASE(4); SS_CASE(5); SS_CASE(6); SS_CASE(7); SS_CASE(8);
+        SS_CASE(9); SS_CASE(10); SS_CASE(11); SS_CASE(12); SS_CASE(13); SS_CASE(14); SS_CASE(15); SS_CASE(16);
+        default: return launch_vote_any(packed, M, voted, d, stream);
+    }
+#undef SS_CASE
+}
+
+int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d, void *hip_stream) {
+    if (d == 0) return SS_OK;
+    if (!x || !bits) return SS_ERR_NULL;
+    if (!aligned16(x) || !aligned16(bits)) return SS_ERR_ALIGN;
+    constexpr int R = 4;
+    const Tiling t = make_tiling(d, R, false);
+    ss::ApplyArgs a;
+    a.x = x;
+    a.bits = bits;
+    a.delta = delta;
+    a.d = d;
+    a.n_tiles = t.n_tiles;
+    const size_t grid = t.n_tiles + t.tail_blocks;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::apply_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
+    return launch_status();
+}
+
+int ss_signum_vote_step(const void *const *g, ss_dtype gdt, float *const *m, int M, float beta, float delta,
+                        float *x, uint32_t *voted, uint32_t *const *packed_out, size_t d, void *hip_stream) {
+    if (M < 1 || M > SS_MAX_WORKERS) return SS_ERR_BAD_M;
+    if (gdt != SS_F32 && gdt != SS_BF16) return SS_ERR_DTYPE;
+    if (d == 0) return SS_OK;
+    if (!g || !x || !voted) return SS_ERR_NULL;
+    for (int w = 0; w < M; ++w) {
+        if (!g[w]) return SS_ERR_NULL;
+        if (m && !m[w]) return SS_ERR_NULL;
+        if (packed_out && !packed_out[w]) return SS_ERR_NULL;
+    }
+    if (!aligned16(x) || !aligned16(voted)) return SS_ERR_ALIGN;
+    for (int w = 0; w < M; ++w) {
+        if (!aligned16(g[w])) return SS_ERR_ALIGN;
+        if (m && !aligned16(m[w])) return SS_ERR_ALIGN;
+        if (packed_out && !aligned16(packed_out[w])) return SS_ERR_ALIGN;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (m) {
+        if (gdt == SS_F32)
+            return launch_step<true, ss::F32Grad>(M, g, m, packed_out, beta, delta, x, voted, d, stream);
+        return launch_step<true, ss::Bf16Grad>(M, g, m, packed_out, beta, delta, x, voted, d, stream);
+    }
+    if (gdt == SS_F32)
+        return launch_step<false, ss::F32Grad>(M, g, m, packed_out, beta, delta, x, voted, d, stream);
+    return launch_step<false, ss::Bf16Grad>(M, g, m, packed_out, beta, delta, x, voted, d, stream);
+}
+
+int ss_stream_copy(void *dst, const void *src, size_t nbytes, void *hip_stream) {
+    if (nbytes == 0) return SS_OK;
+    if (!dst || !src) return SS_ERR_NULL;
+    if (!aligned16(dst) || !aligned16(src)) return SS_ERR_ALIGN;
+    if (nbytes % 16 != 0) return SS_ERR_ARG;
+    const size_t n_vec = nbytes / 16;
+    const size_t grid = (n_vec + ss::kBlock * 4 - 1) / (ss::kBlock * 4);
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::copy_kernel<<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(
+        static_cast<ss::f32x4 *>(dst), static_cast<const ss::f32x4 *>(src), n_vec);
+    return launch_status();
+}
+
+}  // extern "C"

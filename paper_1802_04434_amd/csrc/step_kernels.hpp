@@ -1,0 +1,154 @@
+// The streaming kernel behind ss_signum_vote_step and ss_signum_pack.
+//
+// One template covers both: per worker the momentum update and sign of
+// Algorithm 2 (or the plain sign of Algorithm 1), the optional per-worker
+// packed bits, and - when VOTE is set - the majority vote and parameter
+// update of Algorithm 3, all while each gradient, momentum and parameter
+// element is read once and written once (arxiv 1802.04434).
+//
+// The path is bound by HBM traffic (12 bytes per worker and coordinate plus
+// 8 for x, against a handful of ALU operations), so the kernel's only job is
+// to keep many independent 128-bit loads in flight: all loads of a batch of
+// workers are issued into registers before the first dependent operation or
+// store, because a store to one worker's momentum could alias (as far as the
+// compiler knows) the next worker's loads and would otherwise serialise them.
+#pragma once
+#include "common.hpp"
+
+namespace ss {
+
+template <int NPTR>
+struct StepArgs {
+    PtrTable<NPTR> p;
+    float *x;            // VOTE only
+    uint32_t *voted;     // VOTE only
+    float beta, omb, delta;
+    int M;               // number of workers in use (<= NPTR)
+    int write_packed;    // per-worker bits wanted
+    size_t d;            // coordinates
+    size_t n_tiles;      // blocks that run the vector path (R rows of 1024 coordinates each)
+    size_t words_total;  // words of a packed buffer including zero padding
+};
+
+// byte-wise counters: bit k of a nibble -> +1 in byte k
+__device__ __forceinline__ uint32_t spread_nibble(uint32_t nib) {
+    return (nib * 0x00204081u) & 0x01010101u;
+}
+
+// bits of the vote: byte k of `counts` holds how many workers are "-" at
+// coordinate k of the quad; "-" wins iff that count reaches T = floor(M/2)+1
+__device__ __forceinline__ uint32_t vote_nibble(uint32_t counts, int T) {
+    uint32_t nib = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) nib |= (((counts >> (8 * k)) & 0xFFu) >= (uint32_t)T ? 1u : 0u) << k;
+    return nib;
+}
+
+// MT  > 0: number of workers known at compile time (M == MT)
+// MT == 0: a.M workers, looped at run time in batches of BW
+// BW     : workers whose loads are issued together
+// R      : rows (of 1024 coordinates) per block
+template <int MT, int NPTR, int BW, int R, bool HAS_M, bool VOTE, typename G>
+__global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int M = MT > 0 ? MT : a.M;
+    const int T = M / 2 + 1;
+    const size_t tile = blockIdx.x;
+
+    if (tile < a.n_tiles) {
+        size_t q[R];
+        uint32_t counts[R];
+        f32x4 xv[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            q[r] = (tile * R + r) * kBlock + tid;
+            counts[r] = 0;
+            if (VOTE) xv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.x) + q[r]);
+        }
+        for (int w0 = 0; w0 < M; w0 += BW) {
+            f32x4 gv[R][BW], mv[R][BW];
+#pragma unroll
+            for (int j = 0; j < BW; ++j) {
+                if (w0 + j < M) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        gv[r][j] = G::load4(a.p.g[w0 + j], q[r]);
+                        if (HAS_M) mv[r][j] = ld_stream(reinterpret_cast<const f32x4 *>(a.p.m[w0 + j]) + q[r]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < BW; ++j) {
+                if (w0 + j < M) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        f32x4 v = gv[r][j];
+                        if (HAS_M) {
+                            f32x4 m0 = mv[r][j];
+                            v.x = momentum(a.beta, a.omb, m0.x, v.x);
+                            v.y = momentum(a.beta, a.omb, m0.y, v.y);
+                            v.z = momentum(a.beta, a.omb, m0.z, v.z);
+                            v.w = momentum(a.beta, a.omb, m0.w, v.w);
+                            st_stream(reinterpret_cast<f32x4 *>(a.p.m[w0 + j]) + q[r], v);
+                        }
+                        const uint32_t nib = neg_nibble(v);
+                        counts[r] += spread_nibble(nib);
+                        if (a.write_packed) {
+                            const uint32_t word = combine8(nib, lane);
+                            if ((lane & 7) == 0) a.p.packed[w0 + j][q[r] >> 3] = word;
+                        }
+                    }
+                }
+            }
+        }
+        if (VOTE) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint32_t nib = vote_nibble(counts[r], T);
+                f32x4 v = xv[r];
+                v.x = step(v.x, a.delta, nib & 1u);
+                v.y = step(v.y, a.delta, nib & 2u);
+                v.z = step(v.z, a.delta, nib & 4u);
+                v.w = step(v.w, a.delta, nib & 8u);
+                st_stream(reinterpret_cast<f32x4 *>(a.x) + q[r], v);
+                const uint32_t word = combine8(nib, lane);
+                if ((lane & 7) == 0) a.voted[q[r] >> 3] = word;
+            }
+        }
+        return;
+    }
+
+    // Scalar path for what does not fill a tile: one coordinate per lane, so
+    // the 64-bit wave ballot is two packed words in order.  It also writes
+    // the zero padding words.
+    const size_t i = a.n_tiles * (size_t)(R * kRowCoords) + (tile - a.n_tiles) * kBlock + tid;
+    const bool in = i < a.d;
+    const size_t word = i >> 5;   // for lanes 0 and 32: the word this half-wave fills
+    const bool writes_word = (lane & 31) == 0 && word < a.words_total;
+    int count = 0;
+    for (int w = 0; w < M; ++w) {
+        float v = 0.0f;
+        if (in) {
+            v = G::load1(a.p.g[w], i);
+            if (HAS_M) {
+                v = momentum(a.beta, a.omb, a.p.m[w][i], v);
+                a.p.m[w][i] = v;
+            }
+        }
+        const bool neg = in && v < 0.0f;
+        count += neg ? 1 : 0;
+        if (a.write_packed) {
+            const uint64_t mask = __builtin_amdgcn_ballot_w64(neg);
+            if (writes_word) a.p.packed[w][word] = (uint32_t)(lane == 0 ? mask : mask >> 32);
+        }
+    }
+    if (VOTE) {
+        const bool vneg = in && count >= T;
+        if (in) a.x[i] = step(a.x[i], a.delta, vneg);
+        const uint64_t mask = __builtin_amdgcn_ballot_w64(vneg);
+        if (writes_word) a.voted[word] = (uint32_t)(lane == 0 ? mask : mask >> 32);
+    }
+}
+
+}  // namespace ss

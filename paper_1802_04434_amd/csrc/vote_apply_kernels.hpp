@@ -1,0 +1,201 @@
+// Stand-alone kernels of the three-call path: the server's majority vote over
+// packed sign words and the worker's parameter update from packed bits
+// (arxiv 1802.04434, Algorithm 3; Algorithm 1 when the bits are one worker's).
+#pragma once
+#include "common.hpp"
+
+namespace ss {
+
+// ---------------------------------------------------------------- vote ----
+// Bit-sliced: a 32-bit word holds 32 coordinates of one worker; the M
+// workers' words for the same coordinates are added "vertically" with
+// carry-save adders into the binary planes of the per-coordinate count of "-"
+// votes, and the count is compared with the constant threshold
+// T = floor(M/2)+1 plane by plane.  32 coordinates per ALU lane-operation.
+
+struct Sum2 { uint32_t sum, carry; };
+__device__ __forceinline__ Sum2 full_add(uint32_t a, uint32_t b, uint32_t c) {
+    const uint32_t ab = a ^ b;
+    return {ab ^ c, (a & b) | (ab & c)};
+}
+__device__ __forceinline__ Sum2 half_add(uint32_t a, uint32_t b) { return {a ^ b, a & b}; }
+
+// count >= T decided from the least significant plane upwards:
+// ge_k = plane_k > T_k, or equal and ge_(k-1)
+__device__ __forceinline__ uint32_t ge_step(uint32_t ge, uint32_t plane, int T, int k) {
+    return ((T >> k) & 1) ? (plane & ge) : (plane | ge);
+}
+
+// N words of weight 2^K: reduce to one word (plane K) and N/2 carries of
+// weight 2^(K+1), fold plane K into the comparison, recurse on the carries.
+template <int N, int K, int T>
+struct CsaLevel {
+    static __device__ __forceinline__ uint32_t run(const uint32_t (&w)[N], uint32_t ge) {
+        constexpr int kFull = (N - 1) / 2;
+        constexpr int kNext = N / 2;
+        uint32_t next[kNext > 0 ? kNext : 1];
+        uint32_t acc = w[0];
+#pragma unroll
+        for (int j = 0; j < kFull; ++j) {
+            const Sum2 s = full_add(acc, w[1 + 2 * j], w[2 + 2 * j]);
+            acc = s.sum;
+            next[j] = s.carry;
+        }
+        if constexpr (N % 2 == 0) {
+            const Sum2 s = half_add(acc, w[N - 1]);
+            acc = s.sum;
+            next[kFull] = s.carry;
+        }
+        ge = ge_step(ge, acc, T, K);
+        if constexpr (kNext > 0) {
+            return CsaLevel<kNext, K + 1, T>::run(next, ge);
+        } else {
+            return ge;
+        }
+    }
+};
+
+// bit set where at least floor(M/2)+1 of the M words have it set
+template <int M>
+__device__ __forceinline__ uint32_t majority_word(const uint32_t (&w)[M]) {
+    return CsaLevel<M, 0, M / 2 + 1>::run(w, 0xFFFFFFFFu);
+}
+
+template <int NPTR>
+struct VoteArgs {
+    const uint32_t *packed[NPTR];
+    uint32_t *voted;
+    int M;
+    size_t d;
+    size_t n_vec;   // 128-bit groups of words, padding included
+};
+
+// bits of word `wi` that lie below coordinate d
+__device__ __forceinline__ uint32_t live_mask(size_t wi, size_t d) {
+    const size_t lo = wi * 32;
+    if (lo + 32 <= d) return 0xFFFFFFFFu;
+    if (lo >= d) return 0u;
+    return (1u << (unsigned)(d - lo)) - 1u;
+}
+
+template <int M>
+__global__ __launch_bounds__(kBlock) void vote_kernel(const VoteArgs<M> a) {
+    const size_t u = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (u >= a.n_vec) return;
+    u32x4 in[M];
+#pragma unroll
+    for (int w = 0; w < M; ++w) in[w] = ld_stream(reinterpret_cast<const u32x4 *>(a.packed[w]) + u);
+    uint32_t col[M];
+    u32x4 out;
+#pragma unroll
+    for (int w = 0; w < M; ++w) col[w] = in[w].x;
+    out.x = majority_word<M>(col) & live_mask(4 * u + 0, a.d);
+#pragma unroll
+    for (int w = 0; w < M; ++w) col[w] = in[w].y;
+    out.y = majority_word<M>(col) & live_mask(4 * u + 1, a.d);
+#pragma unroll
+    for (int w = 0; w < M; ++w) col[w] = in[w].z;
+    out.z = majority_word<M>(col) & live_mask(4 * u + 2, a.d);
+#pragma unroll
+    for (int w = 0; w < M; ++w) col[w] = in[w].w;
+    out.w = majority_word<M>(col) & live_mask(4 * u + 3, a.d);
+    st_stream(reinterpret_cast<u32x4 *>(a.voted) + u, out);
+}
+
+// Any M up to SS_MAX_WORKERS: the count planes are kept in seven registers
+// and every word is added with a ripple of half adders.
+constexpr int kPlanes = 7;   // counts up to 64 < 2^7
+
+__global__ __launch_bounds__(kBlock) void vote_kernel_any(const VoteArgs<64> a) {
+    const size_t u = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (u >= a.n_vec) return;
+    const int T = a.M / 2 + 1;
+    u32x4 plane[kPlanes];
+#pragma unroll
+    for (int k = 0; k < kPlanes; ++k) plane[k] = u32x4{0, 0, 0, 0};
+    constexpr int kBatch = 8;
+    for (int w0 = 0; w0 < a.M; w0 += kBatch) {
+        u32x4 in[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j)
+            if (w0 + j < a.M) in[j] = ld_stream(reinterpret_cast<const u32x4 *>(a.packed[w0 + j]) + u);
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            if (w0 + j < a.M) {
+                u32x4 carry = in[j];
+#pragma unroll
+                for (int k = 0; k < kPlanes; ++k) {
+                    const u32x4 t = plane[k] & carry;
+                    plane[k] ^= carry;
+                    carry = t;
+                }
+            }
+        }
+    }
+    u32x4 ge = u32x4{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+#pragma unroll
+    for (int k = 0; k < kPlanes; ++k) ge = ((T >> k) & 1) ? (plane[k] & ge) : (plane[k] | ge);
+    ge.x &= live_mask(4 * u + 0, a.d);
+    ge.y &= live_mask(4 * u + 1, a.d);
+    ge.z &= live_mask(4 * u + 2, a.d);
+    ge.w &= live_mask(4 * u + 3, a.d);
+    st_stream(reinterpret_cast<u32x4 *>(a.voted) + u, ge);
+}
+
+// --------------------------------------------------------------- apply ----
+
+struct ApplyArgs {
+    float *x;
+    const uint32_t *bits;
+    float delta;
+    size_t d;
+    size_t n_tiles;   // blocks on the vector path, R rows each
+};
+
+template <int R>
+__global__ __launch_bounds__(kBlock) void apply_kernel(const ApplyArgs a) {
+    const int tid = threadIdx.x;
+    const size_t tile = blockIdx.x;
+    if (tile < a.n_tiles) {
+        size_t q[R];
+        f32x4 xv[R];
+        uint32_t word[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            q[r] = (tile * R + r) * kBlock + tid;
+            xv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.x) + q[r]);
+            word[r] = a.bits[q[r] >> 3];   // 8 lanes share a word
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint32_t nib = word[r] >> ((tid & 7) * 4);
+            f32x4 v = xv[r];
+            v.x = step(v.x, a.delta, nib & 1u);
+            v.y = step(v.y, a.delta, nib & 2u);
+            v.z = step(v.z, a.delta, nib & 4u);
+            v.w = step(v.w, a.delta, nib & 8u);
+            st_stream(reinterpret_cast<f32x4 *>(a.x) + q[r], v);
+        }
+        return;
+    }
+    const size_t i = a.n_tiles * (size_t)(R * kRowCoords) + (tile - a.n_tiles) * kBlock + tid;
+    if (i < a.d) {
+        const bool neg = (a.bits[i >> 5] >> (i & 31)) & 1u;
+        a.x[i] = step(a.x[i], a.delta, neg);
+    }
+}
+
+// ---------------------------------------------------------------- copy ----
+
+__global__ __launch_bounds__(kBlock) void copy_kernel(f32x4 *dst, const f32x4 *src, size_t n_vec) {
+    const size_t base = (size_t)blockIdx.x * (kBlock * 4) + threadIdx.x;
+    f32x4 v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (base + r * kBlock < n_vec) v[r] = ld_stream(src + base + r * kBlock);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (base + r * kBlock < n_vec) st_stream(dst + base + r * kBlock, v[r]);
+}
+
+}  // namespace ss

@@ -1,0 +1,98 @@
+"""Host-only checks of the C-ABI HIP library: it loads, exports every symbol the
+header declares, and rejects bad arguments before anything is launched.  No
+kernel runs here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "signsgd.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_1802_04434_amd as ss
+    return ss.load_library()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ss_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"ss_signum_pack", "ss_majority_vote", "ss_sign_apply", "ss_signum_vote_step",
+            "ss_packed_words", "ss_packed_bytes", "ss_last_hip_error"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_packed_sizes(lib):
+    for d, words, nbytes in ((0, 0, 0), (1, 1, 16), (32, 1, 16), (33, 2, 16), (128, 4, 16), (129, 5, 32),
+                             (25_557_032, 798_658, 3_194_640), (1_500_000_017, 46_875_001, 187_500_016)):
+        assert lib.ss_packed_words(d) == words
+        assert lib.ss_packed_bytes(d) == nbytes
+
+
+def test_argument_errors_come_back_as_status_codes(lib):
+    OK, NULL, BAD_M, ALIGN, DTYPE = 0, -1, -2, -3, -4
+    a = ctypes.c_void_p(0x1000)        # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1004)
+    one = (ctypes.c_void_p * 1)(0x1000)
+    one_odd = (ctypes.c_void_p * 1)(0x1008)
+    one_null = (ctypes.c_void_p * 1)(None)
+    # d == 0: nothing to do, even with null pointers
+    assert lib.ss_signum_pack(None, 0, None, 0.9, None, 0, None) == OK
+    assert lib.ss_majority_vote(None, 1, None, 0, None) == OK
+    assert lib.ss_sign_apply(None, None, 0.1, 0, None) == OK
+    assert lib.ss_signum_vote_step(None, 0, None, 1, 0.9, 0.1, None, None, None, 0, None) == OK
+    # dtype
+    assert lib.ss_signum_pack(a, 2, None, 0.9, a, 8, None) == DTYPE
+    assert lib.ss_signum_vote_step(one, -1, None, 1, 0.9, 0.1, a, a, None, 8, None) == DTYPE
+    # worker count
+    for M in (0, -3, 65):
+        assert lib.ss_majority_vote(one, M, a, 8, None) == BAD_M
+        assert lib.ss_signum_vote_step(one, 0, None, M, 0.9, 0.1, a, a, None, 8, None) == BAD_M
+    # null pointers
+    assert lib.ss_signum_pack(None, 0, None, 0.9, a, 8, None) == NULL
+    assert lib.ss_signum_pack(a, 0, None, 0.9, None, 8, None) == NULL
+    assert lib.ss_majority_vote(None, 1, a, 8, None) == NULL
+    assert lib.ss_majority_vote(one_null, 1, a, 8, None) == NULL
+    assert lib.ss_majority_vote(one, 1, None, 8, None) == NULL
+    assert lib.ss_sign_apply(None, a, 0.1, 8, None) == NULL
+    assert lib.ss_sign_apply(a, None, 0.1, 8, None) == NULL
+    assert lib.ss_signum_vote_step(None, 0, None, 1, 0.9, 0.1, a, a, None, 8, None) == NULL
+    assert lib.ss_signum_vote_step(one_null, 0, None, 1, 0.9, 0.1, a, a, None, 8, None) == NULL
+    assert lib.ss_signum_vote_step(one, 0, one_null, 1, 0.9, 0.1, a, a, None, 8, None) == NULL
+    assert lib.ss_signum_vote_step(one, 0, None, 1, 0.9, 0.1, None, a, None, 8, None) == NULL
+    assert lib.ss_signum_vote_step(one, 0, None, 1, 0.9, 0.1, a, None, None, 8, None) == NULL
+    assert lib.ss_signum_vote_step(one, 0, None, 1, 0.9, 0.1, a, a, one_null, 8, None) == NULL
+    # alignment
+    assert lib.ss_signum_pack(odd, 0, None, 0.9, a, 8, None) == ALIGN
+    assert lib.ss_signum_pack(a, 0, odd, 0.9, a, 8, None) == ALIGN
+    assert lib.ss_signum_pack(a, 0, None, 0.9, odd, 8, None) == ALIGN
+    assert lib.ss_majority_vote(one_odd, 1, a, 8, None) == ALIGN
+    assert lib.ss_majority_vote(one, 1, odd, 8, None) == ALIGN
+    assert lib.ss_sign_apply(odd, a, 0.1, 8, None) == ALIGN
+    assert lib.ss_sign_apply(a, odd, 0.1, 8, None) == ALIGN
+    assert lib.ss_signum_vote_step(one_odd, 0, None, 1, 0.9, 0.1, a, a, None, 8, None) == ALIGN
+    assert lib.ss_signum_vote_step(one, 0, one_odd, 1, 0.9, 0.1, a, a, None, 8, None) == ALIGN
+    assert lib.ss_signum_vote_step(one, 0, None, 1, 0.9, 0.1, odd, a, None, 8, None) == ALIGN
+    assert lib.ss_signum_vote_step(one, 0, None, 1, 0.9, 0.1, a, odd, None, 8, None) == ALIGN
+    assert lib.ss_signum_vote_step(one, 0, None, 1, 0.9, 0.1, a, a, one_odd, 8, None) == ALIGN
+    assert lib.ss_stream_copy(a, a, 24, None) == -5
+    assert lib.ss_last_hip_error() == 0
+
+
+def test_product_package_does_not_reach_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1802_04434_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower().replace("no fallback", ""), f
+                assert "sso_" not in text, f
