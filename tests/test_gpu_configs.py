@@ -1,0 +1,170 @@
+"""GPU parity on the five benchmark workloads at their FULL sizes, in the launch
+configuration bench.py times (fused ss_signum_vote_step).
+
+Two kinds of check per step:
+  * against the CPU oracle, bit for bit, on whole chunks of coordinates (all of
+    them for C1-C3; the first, the last ragged one and a few seeded ones for
+    C4 and C5).  Coordinates do not interact, so the oracle can follow a chunk
+    through every step on its own.
+  * on EVERY coordinate, properties that hold at any size, evaluated with plain
+    torch operations on the device: each worker's bit is [m_w < 0], the voted
+    bit is [2 * (number of "-" workers) > M], and x moved by exactly -delta or
+    +delta according to its voted bit (rounded once); padding bits are zero.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+SLAB = 8     # chunks checked together on the device
+
+
+@pytest.fixture(scope="module")
+def ss():
+    import paper_1802_04434_amd as lib
+    lib.load_library()
+    return lib
+
+
+def unpack_device(bits_i32, n):
+    """first n bits of a device int32 word tensor as a bool tensor"""
+    shifts = torch.arange(32, device=bits_i32.device, dtype=torch.int32)
+    return ((bits_i32.unsqueeze(1) >> shifts) & 1).bool().reshape(-1)[:n]
+
+
+def fill_gradients(cfg, step, g, mus, ties):
+    for c in range(cfg.n_chunks):
+        lo, hi = cfg.chunk_range(c)
+        mu = mus[c] if mus is not None else synth.mu_chunk(cfg, c, DEV)
+        tie = ties[c] if ties is not None else None
+        for w in range(cfg.M):
+            g[w][lo:hi] = synth.grad_chunk(cfg, step, w, c, DEV, mu=mu, tie=tie)
+
+
+def run_config(ss, oracle, cfg, oracle_chunks, threads=16):
+    d, M = cfg.d, cfg.M
+    has_m = cfg.beta is not None
+    beta = cfg.beta if has_m else 0.0
+    gdtype = torch.float32 if cfg.grad_dtype == "f32" else torch.bfloat16
+    n_words = ss.packed_bytes(d) // 4
+    g = [torch.empty(d, device=DEV, dtype=gdtype) for _ in range(M)]
+    m = [torch.zeros(d, device=DEV) for _ in range(M)] if has_m else None
+    x = torch.empty(d, device=DEV)
+    for c in range(cfg.n_chunks):
+        lo, hi = cfg.chunk_range(c)
+        x[lo:hi] = synth.x0_chunk(cfg, c, DEV)
+    x_before = torch.empty_like(x)
+    # mean gradients and tie sets are fixed over steps: keep them when they fit comfortably
+    keep = d <= 200_000_000
+    mus = [synth.mu_chunk(cfg, c, DEV) for c in range(cfg.n_chunks)] if keep else None
+    ties = [synth.tie_chunk(cfg, c, DEV) for c in range(cfg.n_chunks)] if (keep and cfg.tie_frac > 0) else None
+    voted = ss.new_bits(d, DEV)
+    packed = [ss.new_bits(d, DEV) for _ in range(M)]
+
+    # oracle state per followed chunk
+    host = {}
+    for c in oracle_chunks:
+        lo, hi = cfg.chunk_range(c)
+        host[c] = {"m": [np.zeros(hi - lo, np.float32) for _ in range(M)] if has_m else None,
+                   "x": x[lo:hi].cpu().numpy().copy()}
+
+    delta_t = torch.tensor(cfg.delta, dtype=torch.float32, device=DEV)
+    forced_ties_seen = 0
+    for k in range(cfg.steps):
+        fill_gradients(cfg, k, g, mus, ties)
+        x_before.copy_(x)
+        voted.fill_(-1)
+        with_packed = (k % 2 == 1) or k == 0
+        if with_packed:
+            for p in packed:
+                p.fill_(-1)
+        print("step", k, cfg.name, "packed_out" if with_packed else "voted only", flush=True)
+        ss.signum_vote_step(g, m, beta, cfg.delta, x, voted, packed if with_packed else None)
+        torch.cuda.synchronize()
+
+        # ---- every coordinate: internal consistency on the device
+        for c0 in range(0, cfg.n_chunks, SLAB):
+            lo = c0 * synth.CHUNK
+            hi = min(d, (c0 + SLAB) * synth.CHUNK)
+            n = hi - lo
+            wlo, whi = lo // 32, (hi + 31) // 32
+            count = torch.zeros(n, dtype=torch.int32, device=DEV)
+            for w in range(M):
+                neg = (m[w][lo:hi] if has_m else g[w][lo:hi].float()) < 0
+                count += neg
+                if with_packed:
+                    assert torch.equal(unpack_device(packed[w][wlo:whi], n), neg), ("packed", k, w, c0)
+            vbits = unpack_device(voted[wlo:whi], n)
+            assert torch.equal(vbits, 2 * count > M), ("vote", k, c0)
+            want_x = torch.where(vbits, x_before[lo:hi] + delta_t, x_before[lo:hi] - delta_t)
+            assert torch.equal(x[lo:hi].view(torch.int32), want_x.view(torch.int32)), ("x", k, c0)
+            if ties is not None:
+                for c in range(c0, min(c0 + SLAB, cfg.n_chunks)):
+                    clo, chi = cfg.chunk_range(c)
+                    is_tie = ties[c][0]
+                    assert torch.all(count[clo - lo:chi - lo][is_tie] * 2 == M), ("forced tie split", k, c)
+                    assert not torch.any(vbits[clo - lo:chi - lo][is_tie]), ("tie votes +", k, c)
+                    forced_ties_seen += int(is_tie.sum())
+        # padding: bits at and beyond d, and pad words, are zero
+        last = voted[d // 32:].cpu().numpy().view(np.uint32)
+        big = sum(int(v) << (32 * i) for i, v in enumerate(last))
+        assert big >> (d % 32) == 0
+        assert n_words * 4 == ss.packed_bytes(d)
+
+        # ---- followed chunks: bit-exact against the oracle
+        for c in oracle_chunks:
+            lo, hi = cfg.chunk_range(c)
+            n = hi - lo
+            st = host[c]
+            gh = [synth.as_numpy(g[w][lo:hi]) for w in range(M)]
+            want_voted, want_packed = oracle.signum_vote_step(gh, st["m"], beta, cfg.delta, st["x"],
+                                                              want_packed=True, threads=threads)
+            nw = len(want_voted)
+            got = voted[lo // 32: lo // 32 + nw].cpu().numpy().view(np.uint32)
+            assert np.array_equal(got, want_voted), ("oracle voted", k, c)
+            if with_packed:
+                for w in range(M):
+                    got = packed[w][lo // 32: lo // 32 + nw].cpu().numpy().view(np.uint32)
+                    assert np.array_equal(got, want_packed[w]), ("oracle packed", k, c, w)
+            if has_m:
+                for w in range(M):
+                    assert np.array_equal(m[w][lo:hi].cpu().numpy().view(np.uint32),
+                                          st["m"][w].view(np.uint32)), ("oracle m", k, c, w)
+            assert np.array_equal(x[lo:hi].cpu().numpy().view(np.uint32), st["x"].view(np.uint32)), \
+                ("oracle x", k, c)
+    if ties is not None:
+        assert forced_ties_seen > 0.08 * d * cfg.steps
+    del g, m, x, x_before, packed, voted
+    torch.cuda.empty_cache()
+
+
+def sampled_chunks(cfg, extra=3):
+    rng = np.random.default_rng(cfg.config_id)
+    n = cfg.n_chunks
+    picks = {0, n - 1} | {int(v) for v in rng.integers(1, max(2, n - 1), extra)}
+    return sorted(c for c in picks if c < n)
+
+
+def test_c1_tiny_signum_vote_every_coordinate(ss, oracle):
+    run_config(ss, oracle, synth.C1, list(range(synth.C1.n_chunks)))
+
+
+def test_c2_signsgd_single_worker_every_coordinate(ss, oracle):
+    # Algorithm 1: no momentum buffer, 5 % exact zeros plus planted -0.0 / subnormals
+    run_config(ss, oracle, synth.C2, list(range(synth.C2.n_chunks)))
+
+
+def test_c3_signum_vote_headline_every_coordinate(ss, oracle):
+    run_config(ss, oracle, synth.C3, list(range(synth.C3.n_chunks)))
+
+
+def test_c4_even_m_ties_full_size(ss, oracle):
+    run_config(ss, oracle, synth.C4, sampled_chunks(synth.C4))
+
+
+def test_c5_bf16_large_full_size(ss, oracle):
+    assert synth.C5.d % 32 == 17 and synth.C5.d % 4 == 1
+    run_config(ss, oracle, synth.C5, sampled_chunks(synth.C5, extra=2))
