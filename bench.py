@@ -120,8 +120,10 @@ def main():
     e1.record(stream)
     torch.cuda.synchronize()
     extra["three_call_path_ms"] = e0.elapsed_time(e1) / n3
-    nb = min(g[0].numel() * g[0].element_size() // 16 * 16, 1 << 30)
-    src, dst = g[0], torch.empty_like(g[0])
+    # 1 GiB each way: far beyond the 256 MB memory-side cache, so an HBM figure
+    nb = 1 << 30
+    src = torch.empty(nb // 4, device=dev).normal_()
+    dst = torch.empty_like(src)
     for _ in range(3):
         ss.stream_copy(dst, src, nb, stream=stream)
     e0.record(stream)
@@ -130,7 +132,8 @@ def main():
     e1.record(stream)
     torch.cuda.synchronize()
     extra["stream_copy_GBs"] = 2 * nb * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del packed, dst
+    extra["stream_copy_bytes_each_way"] = nb
+    del packed, dst, src
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -42,63 +42,38 @@ inline Tiling make_tiling(size_t d, int rows, bool covers_padding) {
 }
 
 // ------------------------------------------------------------------------
-// Launch shapes.  R = rows of 1024 coordinates per block, BW = workers whose
-// loads are in flight together.  A lane keeps 2*BW*R (momentum) or BW*R
-// (no momentum) 128-bit loads in flight, plus R for x.
-#ifdef SS_FORCE_ROWS
-constexpr int rows_for(int, bool) { return SS_FORCE_ROWS; }
-#else
-constexpr int rows_for(int m, bool has_m) {
+// Launch shapes of the step kernel (see step_kernels.hpp for the reasoning).
+//   streaming shape, d >= kStreamingMinD: one worker at a time (BW = 1),
+//     kStreamRows rows per block, kStreamLdsHold bytes of LDS held per block
+//     so that two blocks share a compute unit (~32 KB of loads in flight)
+//   latency shape, smaller d: all workers' loads at once, no cap
+#ifndef SS_STREAM_ROWS
+#define SS_STREAM_ROWS 2
+#endif
+#ifndef SS_STREAM_LDS_HOLD
+#define SS_STREAM_LDS_HOLD (80 * 1024)
+#endif
+#ifndef SS_STREAM_MIN_D
+#define SS_STREAM_MIN_D (4u << 20)
+#endif
+constexpr int kStreamRows = SS_STREAM_ROWS;
+constexpr int kStreamLdsHold = SS_STREAM_LDS_HOLD;
+constexpr size_t kStreamingMinD = SS_STREAM_MIN_D;
+
+constexpr int latency_rows(int m, bool has_m) {
     const int streams = m * (has_m ? 2 : 1);
     return streams >= 8 ? 1 : streams >= 4 ? 2 : 4;
 }
-#endif
-#ifdef SS_FORCE_BATCH
-constexpr int batch_for(int m) { return m < SS_FORCE_BATCH ? m : SS_FORCE_BATCH; }
-#else
-constexpr int batch_for(int m) { return m < 8 ? m : 8; }
-#endif
+constexpr int latency_batch(int m) { return m < 8 ? m : 8; }
 
-template <int MT, bool HAS_M, bool VOTE, typename G>
-int launch_step_fixed(const void *const *g, float *const *m, uint32_t *const *packed, float beta,
-                      float delta, float *x, uint32_t *voted, size_t d, hipStream_t stream) {
-    constexpr int R = rows_for(MT, HAS_M);
-    constexpr int BW = batch_for(MT);
-    ss::StepArgs<MT> a;
-    for (int w = 0; w < MT; ++w) {
-        a.p.g[w] = g[w];
-        a.p.m[w] = HAS_M ? m[w] : nullptr;
-        a.p.packed[w] = packed ? packed[w] : nullptr;
-    }
-    const Tiling t = make_tiling(d, R, true);
-    a.x = x;
-    a.voted = voted;
-    a.beta = beta;
-    a.omb = 1.0f - beta;
-    a.delta = delta;
-    a.M = MT;
-    a.write_packed = packed != nullptr;
-    a.d = d;
-    a.n_tiles = t.n_tiles;
-    a.words_total = t.words_total;
-    const size_t grid = t.n_tiles + t.tail_blocks;
-    if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::step_kernel<MT, MT, BW, R, HAS_M, VOTE, G><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
-    return launch_status();
-}
-
-template <bool HAS_M, typename G>
-int launch_step_any(int M, const void *const *g, float *const *m, uint32_t *const *packed, float beta,
-                    float delta, float *x, uint32_t *voted, size_t d, hipStream_t stream) {
-    constexpr int R = 1;
-    constexpr int BW = 8;
-    ss::StepArgs<SS_MAX_WORKERS> a;
-    for (int w = 0; w < SS_MAX_WORKERS; ++w) {
+template <int NPTR>
+void fill_step_args(ss::StepArgs<NPTR> &a, int M, const void *const *g, float *const *m, uint32_t *const *packed,
+                    float beta, float delta, float *x, uint32_t *voted, size_t d) {
+    for (int w = 0; w < NPTR; ++w) {
         a.p.g[w] = w < M ? g[w] : nullptr;
-        a.p.m[w] = (HAS_M && w < M) ? m[w] : nullptr;
+        a.p.m[w] = (m && w < M) ? m[w] : nullptr;
         a.p.packed[w] = (packed && w < M) ? packed[w] : nullptr;
     }
-    const Tiling t = make_tiling(d, R, true);
     a.x = x;
     a.voted = voted;
     a.beta = beta;
@@ -107,24 +82,43 @@ int launch_step_any(int M, const void *const *g, float *const *m, uint32_t *cons
     a.M = M;
     a.write_packed = packed != nullptr;
     a.d = d;
+}
+
+template <int MT, int NPTR, int BW, int R, int LDS_HOLD, bool HAS_M, bool VOTE, typename G>
+int launch_step_shape(ss::StepArgs<NPTR> &a, size_t d, hipStream_t stream) {
+    const Tiling t = make_tiling(d, R, true);
     a.n_tiles = t.n_tiles;
     a.words_total = t.words_total;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::step_kernel<0, SS_MAX_WORKERS, BW, R, HAS_M, true, G>
+    ss::step_kernel<MT, NPTR, BW, R, LDS_HOLD, HAS_M, VOTE, G>
         <<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
     return launch_status();
+}
+
+// MT > 0: M fixed at compile time; MT == 0: any M up to SS_MAX_WORKERS
+template <int MT, bool HAS_M, bool VOTE, typename G>
+int launch_step_m(int M, const void *const *g, float *const *m, uint32_t *const *packed, float beta, float delta,
+                  float *x, uint32_t *voted, size_t d, hipStream_t stream) {
+    constexpr int NPTR = MT > 0 ? MT : SS_MAX_WORKERS;
+    ss::StepArgs<NPTR> a;
+    fill_step_args<NPTR>(a, M, g, HAS_M ? m : nullptr, packed, beta, delta, x, voted, d);
+    if (d >= kStreamingMinD)
+        return launch_step_shape<MT, NPTR, 1, kStreamRows, kStreamLdsHold, HAS_M, VOTE, G>(a, d, stream);
+    constexpr int R = MT > 0 ? latency_rows(MT, HAS_M) : 1;
+    constexpr int BW = MT > 0 ? latency_batch(MT) : 8;
+    return launch_step_shape<MT, NPTR, BW, R, 0, HAS_M, VOTE, G>(a, d, stream);
 }
 
 template <bool HAS_M, typename G>
 int launch_step(int M, const void *const *g, float *const *m, uint32_t *const *packed, float beta,
                 float delta, float *x, uint32_t *voted, size_t d, hipStream_t stream) {
 #define SS_CASE(n) \
-    case n: return launch_step_fixed<n, HAS_M, true, G>(g, m, packed, beta, delta, x, voted, d, stream)
+    case n: return launch_step_m<n, HAS_M, true, G>(M, g, m, packed, beta, delta, x, voted, d, stream)
     switch (M) {
         SS_CASE(1); SS_CASE(2); SS_CASE(3); SS_CASE(4); SS_CASE(5); SS_CASE(6); SS_CASE(7); SS_CASE(8);
         SS_CASE(16);
-        default: return launch_step_any<HAS_M, G>(M, g, m, packed, beta, delta, x, voted, d, stream);
+        default: return launch_step_m<0, HAS_M, true, G>(M, g, m, packed, beta, delta, x, voted, d, stream);
     }
 #undef SS_CASE
 }
@@ -178,12 +172,12 @@ int ss_signum_pack(const void *g, ss_dtype gdt, float *m, float beta, uint32_t *
     uint32_t *ps[1] = {packed};
     if (m) {
         if (gdt == SS_F32)
-            return launch_step_fixed<1, true, false, ss::F32Grad>(gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
-        return launch_step_fixed<1, true, false, ss::Bf16Grad>(gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+            return launch_step_m<1, true, false, ss::F32Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+        return launch_step_m<1, true, false, ss::Bf16Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
     }
     if (gdt == SS_F32)
-        return launch_step_fixed<1, false, false, ss::F32Grad>(gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
-    return launch_step_fixed<1, false, false, ss::Bf16Grad>(gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+        return launch_step_m<1, false, false, ss::F32Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+    return launch_step_m<1, false, false, ss::Bf16Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
 }
 
 int ss_majority_vote(const uint32_t *const *packed, int M, uint32_t *voted, size_t d, void *hip_stream) {

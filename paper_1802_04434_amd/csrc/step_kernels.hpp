@@ -7,11 +7,24 @@
 // element is read once and written once (arxiv 1802.04434).
 //
 // The path is bound by HBM traffic (12 bytes per worker and coordinate plus
-// 8 for x, against a handful of ALU operations), so the kernel's only job is
-// to keep many independent 128-bit loads in flight: all loads of a batch of
-// workers are issued into registers before the first dependent operation or
-// store, because a store to one worker's momentum could alias (as far as the
-// compiler knows) the next worker's loads and would otherwise serialise them.
+// 8 for x, against a handful of ALU operations).  Two things decide how close
+// to the DRAM's rate it runs, both measured on MI355X:
+//
+//  * Loads of a batch of BW workers are issued into registers before the first
+//    dependent operation or store: a store to one worker's momentum could alias
+//    (as far as the compiler knows) the next worker's loads and would otherwise
+//    serialise them.
+//  * The amount of traffic in flight.  About 32 KB of outstanding loads per
+//    compute unit (8 MB over the chip, the bandwidth-delay product) saturates
+//    HBM; more than that only lengthens the memory system's queues and mixes
+//    more DRAM rows into them, and the rate drops by 5-10 % - the more streams
+//    (workers) the worse.  For large d the kernel therefore walks the workers
+//    ONE AT A TIME (BW = 1, a block touches two input streams and one output
+//    stream at any moment) and caps the resident blocks per compute unit by
+//    having every block hold a slice of LDS it does not otherwise need
+//    (LDS_HOLD bytes; two 256-thread blocks per unit at 80 KB each).
+//    Small d is latency bound instead: there all M workers' loads go out
+//    together (BW = M) and nothing is held back.
 #pragma once
 #include "common.hpp"
 
@@ -26,7 +39,7 @@ struct StepArgs {
     int M;               // number of workers in use (<= NPTR)
     int write_packed;    // per-worker bits wanted
     size_t d;            // coordinates
-    size_t n_tiles;      // blocks that run the vector path (R rows of 1024 coordinates each)
+    size_t n_tiles;      // blocks on the vector path (R rows of kRowCoords coordinates each)
     size_t words_total;  // words of a packed buffer including zero padding
 };
 
@@ -44,17 +57,33 @@ __device__ __forceinline__ uint32_t vote_nibble(uint32_t counts, int T) {
     return nib;
 }
 
+// Occupancy governor: a block that declares BYTES of LDS keeps other blocks
+// off its compute unit (160 KB of LDS per unit on gfx950).  The memory is
+// never used for data; the impossible branch only keeps the allocation alive.
+template <int BYTES>
+__device__ __forceinline__ void hold_lds(bool never, uint32_t *sink) {
+    if constexpr (BYTES > 0) {
+        __shared__ uint32_t held[BYTES / 4];
+        if (never) {
+            held[threadIdx.x] = threadIdx.x;
+            *sink = held[(threadIdx.x * 7) % (BYTES / 4)];
+        }
+    }
+}
+
 // MT  > 0: number of workers known at compile time (M == MT)
 // MT == 0: a.M workers, looped at run time in batches of BW
 // BW     : workers whose loads are issued together
-// R      : rows (of 1024 coordinates) per block
-template <int MT, int NPTR, int BW, int R, bool HAS_M, bool VOTE, typename G>
+// R      : rows (of kRowCoords coordinates) per block
+// LDS_HOLD: bytes of LDS held per block to cap the blocks per compute unit
+template <int MT, int NPTR, int BW, int R, int LDS_HOLD, bool HAS_M, bool VOTE, typename G>
 __global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int M = MT > 0 ? MT : a.M;
     const int T = M / 2 + 1;
     const size_t tile = blockIdx.x;
+    hold_lds<LDS_HOLD>(a.words_total == 0, a.p.packed[0]);   // words_total >= 4 whenever a kernel runs
 
     if (tile < a.n_tiles) {
         size_t q[R];

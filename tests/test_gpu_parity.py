@@ -299,3 +299,31 @@ def test_checkpoint_resume_is_bit_identical(ss):
     a, b = run(False), run(True)
     assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
     assert all(torch.equal(p, q) for p, q in zip(a[0], b[0]))
+
+
+@pytest.mark.parametrize("M,dtype,momentum", [(2, "f32", True), (3, "bf16", True), (4, "f32", False),
+                                              (9, "f32", True), (11, "bf16", False)])
+def test_fused_step_large_d_worker_major_path(ss, oracle, M, dtype, momentum):
+    # large enough that the library sweeps worker by worker with resident
+    # blocks (counts in LDS); ragged so that the scalar tail runs as well
+    d = 9_000_000 + 1234 + 19
+    cfg = synth.Config("large", 40 + M, d, M, dtype, 0.9 if momentum else None, 1e-4, 2, "normal", 0.1, 0.5)
+    m = [np.zeros(d, np.float32) for _ in range(M)] if momentum else None
+    m_dev = [torch.zeros(d, device=DEV) for _ in range(M)] if momentum else None
+    x_dev = torch.cat([synth.x0_chunk(cfg, c, DEV) for c in range(cfg.n_chunks)])
+    x = x_dev.cpu().numpy().copy()
+    for k in range(cfg.steps):
+        g_dev = [torch.cat([synth.grad_chunk(cfg, k, w, c, DEV) for c in range(cfg.n_chunks)]) for w in range(M)]
+        voted = dirty_bits(ss, d)
+        packed = [dirty_bits(ss, d) for _ in range(M)] if k == 1 else None
+        ss.signum_vote_step(g_dev, m_dev, 0.9, 1e-4, x_dev, voted, packed)
+        want_voted, want_bits = oracle.signum_vote_step([synth.as_numpy(t) for t in g_dev], m, 0.9, 1e-4, x,
+                                                        want_packed=True, threads=16)
+        assert np.array_equal(bits_np(voted), want_voted), ("voted", k)
+        if packed is not None:
+            for w in range(M):
+                assert np.array_equal(bits_np(packed[w]), want_bits[w]), ("packed", k, w)
+        if momentum:
+            for w in range(M):
+                assert_same_floats(m_dev[w], m[w], "m[%d] step %d" % (w, k))
+        assert_same_floats(x_dev, x, "x step %d" % k)
