@@ -54,7 +54,7 @@ inline Tiling make_tiling(size_t d, int rows, bool covers_padding) {
 #define SS_STREAM_LDS_HOLD (80 * 1024)
 #endif
 #ifndef SS_STREAM_MIN_D
-#define SS_STREAM_MIN_D (4u << 20)
+#define SS_STREAM_MIN_D (1u << 20)
 #endif
 constexpr int kStreamRows = SS_STREAM_ROWS;
 constexpr int kStreamLdsHold = SS_STREAM_LDS_HOLD;
@@ -103,11 +103,17 @@ int launch_step_m(int M, const void *const *g, float *const *m, uint32_t *const 
     constexpr int NPTR = MT > 0 ? MT : SS_MAX_WORKERS;
     ss::StepArgs<NPTR> a;
     fill_step_args<NPTR>(a, M, g, HAS_M ? m : nullptr, packed, beta, delta, x, voted, d);
-    if (d >= kStreamingMinD)
-        return launch_step_shape<MT, NPTR, 1, kStreamRows, kStreamLdsHold, HAS_M, VOTE, G>(a, d, stream);
-    constexpr int R = MT > 0 ? latency_rows(MT, HAS_M) : 1;
-    constexpr int BW = MT > 0 ? latency_batch(MT) : 8;
-    return launch_step_shape<MT, NPTR, BW, R, 0, HAS_M, VOTE, G>(a, d, stream);
+    if constexpr (MT == 1) {
+        // a single worker is two or three streams whatever the shape: no cap needed
+        constexpr int R = VOTE ? 2 : 4;
+        return launch_step_shape<1, NPTR, 1, R, 0, HAS_M, VOTE, G>(a, d, stream);
+    } else {
+        if (d >= kStreamingMinD)
+            return launch_step_shape<MT, NPTR, 1, kStreamRows, kStreamLdsHold, HAS_M, VOTE, G>(a, d, stream);
+        constexpr int R = MT > 0 ? latency_rows(MT, HAS_M) : 1;
+        constexpr int BW = MT > 0 ? latency_batch(MT) : 8;
+        return launch_step_shape<MT, NPTR, BW, R, 0, HAS_M, VOTE, G>(a, d, stream);
+    }
 }
 
 template <bool HAS_M, typename G>
