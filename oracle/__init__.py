@@ -35,6 +35,11 @@ def lib():
         L.sso_sign_apply.argtypes = [vp, vp, f32, sz]
         L.sso_signum_vote_step.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, sz]
         L.sso_signum_vote_step_mt.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, sz, i32]
+        L.sso_warmup_length.restype = ctypes.c_long
+        L.sso_warmup_length.argtypes = [f32]
+        L.sso_signum_pack_warmup.argtypes = [vp, i32, vp, f32, vp, sz]
+        L.sso_sum_apply.argtypes = [vp, vp, f32, sz]
+        L.sso_signum_vote_step_ex.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, vp, sz, ctypes.c_uint]
         _lib = L
     return _lib
 
@@ -141,3 +146,55 @@ def signum_vote_step(g, m, beta, delta, x, d=None, want_packed=False, threads=1)
     else:
         _check(lib().sso_signum_vote_step_mt(*args, int(threads)), "sso_signum_vote_step_mt")
     return (voted, packed) if want_packed else voted
+
+
+STEP_WARMUP = 1
+STEP_SUM_UPDATE = 2
+
+
+def warmup_length(beta):
+    """Theorem 3's C(beta); raises for beta outside (0, 1)"""
+    c = lib().sso_warmup_length(float(np.float32(beta)))
+    if c < 0:
+        raise ValueError("beta must lie in (0, 1)")
+    return c
+
+
+def signum_pack_warmup(g, m, beta, d=None):
+    d = len(g) if d is None else d
+    gdt = _grad_dtype(g)
+    _need(g, g.dtype, d, "g")
+    if m is not None:
+        _need(m, np.float32, d, "m")
+    packed = new_bits(d)
+    _check(lib().sso_signum_pack_warmup(_ptr(g), gdt, _ptr(m) if m is not None else None,
+                                        float(np.float32(beta)), _ptr(packed), d), "sso_signum_pack_warmup")
+    return packed
+
+
+def sum_apply(x, sums, delta, d=None):
+    d = len(x) if d is None else d
+    _need(x, np.float32, d, "x")
+    _need(sums, np.int8, d, "sums")
+    _check(lib().sso_sum_apply(_ptr(x), _ptr(sums), float(np.float32(delta)), d), "sso_sum_apply")
+
+
+def signum_vote_step_ex(g, m, beta, delta, x, flags, d=None):
+    """returns (voted, packed list, sums int8)"""
+    M = len(g)
+    d = len(x) if d is None else d
+    gdt = _grad_dtype(g[0])
+    for a in g:
+        _need(a, g[0].dtype, d, "g")
+    if m is not None:
+        for a in m:
+            _need(a, np.float32, d, "m")
+    _need(x, np.float32, d, "x")
+    voted = new_bits(d)
+    packed = [new_bits(d) for _ in range(M)]
+    sums = np.empty(d, dtype=np.int8)
+    _check(lib().sso_signum_vote_step_ex(_ptr_array(g), gdt, _ptr_array(m) if m is not None else None, M,
+                                         float(np.float32(beta)), float(np.float32(delta)), _ptr(x), _ptr(voted),
+                                         _ptr_array(packed), _ptr(sums), d, int(flags)),
+           "sso_signum_vote_step_ex")
+    return voted, packed, sums

@@ -18,6 +18,11 @@
  *                     x <- x - delta * sign(...).
  *   sso_signum_vote_step  the three above in sequence over M workers.
  *   sso_vote_sum      the integer sum_m sign(g_m) of Section 4's "(good)".
+ *   sso_sum_apply     Section 4 "(good)": x <- x - delta * sum_m sign(g_m).
+ *   sso_warmup_length Theorem 3's warm-up length C(beta).
+ *   sso_signum_pack_warmup  Theorem 3's warm-up iteration: momentum is
+ *                     accumulated as usual, the sign is taken from the gradient.
+ *   sso_signum_vote_step_ex  the whole step with either or both variants.
  *
  * Readings the paper leaves open, fixed here:
  *   sign(v) = -1 if v < 0, else +1.  Zero (either sign of zero) is "+".
@@ -32,6 +37,11 @@
  *   with momentum and M workers, every worker keeps its own m and votes
  *     with sign(m_m).
  *   bf16 gradients are widened to fp32 exactly before use.
+ *   "(good)" update: x <- fl(x - fl(delta * S)) with the integer sum S
+ *     converted to fp32 exactly; with momentum, S sums sign(m_m).
+ *   C(beta) is evaluated in double precision with beta^C built by repeated
+ *     multiplication; the smallest positive integer meeting both conditions
+ *     of Theorem 3 is returned, exactly as the theorem states it.
  *
  * Parity pins: tests/test_oracle_*.py (brute force on small sizes, exact
  * rational rounding, closed forms and invariants).
@@ -251,4 +261,102 @@ int sso_signum_vote_step_mt(const void *const *g, int gdt, float *const *m,
         }
     }
     return rc_all;
+}
+
+/* ---- variants: Theorem 3's warm-up and Section 4's "(good)" update ---- */
+
+#define SSO_STEP_WARMUP 1
+#define SSO_STEP_SUM_UPDATE 2
+
+/* Theorem 3: C(beta) = min C in Z+ with
+ *   (C/2) beta^C <= 1/(1-beta^2) * 1/(C+1)   and   beta^(C+1) <= 1/2      */
+long sso_warmup_length(float beta_f)
+{
+    double beta = (double)beta_f;
+    if (!(beta > 0.0 && beta < 1.0)) return SSO_ERR_ARG;
+    double pow_c = 1.0; /* beta^C */
+    for (long C = 1; C <= 1000000000L; ++C) {
+        pow_c *= beta;
+        double lhs = (double)C / 2.0 * pow_c;
+        double rhs = 1.0 / (1.0 - beta * beta) * (1.0 / ((double)C + 1.0));
+        if (lhs <= rhs && pow_c * beta <= 0.5) return C;
+    }
+    return SSO_ERR_ARG;
+}
+
+/* Theorem 3, one of the first C(beta) iterations on one worker:
+ * m <- beta m + (1-beta) g as in Algorithm 2, but bit_i <- [sign(g_i) = -1] */
+int sso_signum_pack_warmup(const void *g, int gdt, float *m, float beta,
+                           uint32_t *packed, size_t d)
+{
+    if (gdt != SSO_F32 && gdt != SSO_BF16) return SSO_ERR_DTYPE;
+    if (d == 0) return SSO_OK;
+    if (!g || !packed) return SSO_ERR_NULL;
+    if (m) {
+        /* the momentum line of Algorithm 2; its sign bits are not used */
+        int rc = sso_signum_pack(g, gdt, m, beta, packed, d);
+        if (rc != SSO_OK) return rc;
+    }
+    return sso_signum_pack(g, gdt, NULL, beta, packed, d);
+}
+
+/* Section 4 "(good)": x_i <- x_i - delta * S_i, S_i = sum_m sign_m,i */
+int sso_sum_apply(float *x, const int8_t *sums, float delta, size_t d)
+{
+    if (d == 0) return SSO_OK;
+    if (!x || !sums) return SSO_ERR_NULL;
+    for (size_t i = 0; i < d; ++i) {
+        float t = delta * (float)sums[i];
+        x[i] = x[i] - t;
+    }
+    return SSO_OK;
+}
+
+/* One whole step with the variants selected by flags:
+ *   SSO_STEP_WARMUP      every worker votes with sign(g_m) while its momentum
+ *                        is still updated (Theorem 3)
+ *   SSO_STEP_SUM_UPDATE  x <- x - delta * sum_m sign (Section 4 "(good)")
+ *                        instead of x <- x - delta * sign(sum)
+ * voted always receives the bits of sign(sum); sums_out (NULL or d bytes)
+ * receives the sums. */
+int sso_signum_vote_step_ex(const void *const *g, int gdt, float *const *m,
+                            int M, float beta, float delta, float *x,
+                            uint32_t *voted, uint32_t *const *packed_out,
+                            int8_t *sums_out, size_t d, unsigned flags)
+{
+    if (M < 1 || M > 127) return SSO_ERR_BAD_M;
+    if (gdt != SSO_F32 && gdt != SSO_BF16) return SSO_ERR_DTYPE;
+    if (flags & ~(unsigned)(SSO_STEP_WARMUP | SSO_STEP_SUM_UPDATE)) return SSO_ERR_ARG;
+    if (d == 0) return SSO_OK;
+    if (!g || !x || !voted) return SSO_ERR_NULL;
+
+    size_t bytes = sso_packed_bytes(d);
+    uint32_t **signs = malloc((size_t)M * sizeof *signs);
+    uint32_t *own = packed_out ? NULL : malloc((size_t)M * bytes);
+    int32_t *sums = malloc(d * sizeof *sums);
+    int8_t *sums8 = sums_out ? sums_out : malloc(d);
+    int rc = (signs && (packed_out || own) && sums && sums8) ? SSO_OK : SSO_ERR_ARG;
+    for (int w = 0; w < M && rc == SSO_OK; ++w) {
+        signs[w] = packed_out ? packed_out[w] : own + (size_t)w * (bytes / 4);
+        if (flags & SSO_STEP_WARMUP)
+            rc = sso_signum_pack_warmup(g[w], gdt, m ? m[w] : NULL, beta, signs[w], d);
+        else
+            rc = sso_signum_pack(g[w], gdt, m ? m[w] : NULL, beta, signs[w], d);
+    }
+    if (rc == SSO_OK)
+        rc = sso_majority_vote((const uint32_t *const *)signs, M, voted, d);
+    if (rc == SSO_OK)
+        rc = sso_vote_sum((const uint32_t *const *)signs, M, d, sums);
+    if (rc == SSO_OK) {
+        for (size_t i = 0; i < d; ++i) sums8[i] = (int8_t)sums[i];
+        if (flags & SSO_STEP_SUM_UPDATE)
+            rc = sso_sum_apply(x, sums8, delta, d);
+        else
+            rc = sso_sign_apply(x, voted, delta, d);
+    }
+    if (!sums_out) free(sums8);
+    free(sums);
+    free(own);
+    free(signs);
+    return rc;
 }
