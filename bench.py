@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--variant", default="default", choices=["default", "warmup", "sum", "sum_out"],
+                    help="default: Algorithms 2+3; warmup: Theorem 3 warm-up iteration; sum: '(good)' "
+                         "update; sum_out: '(good)' update that also writes the int8 vote sums")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target length of the oracle timing")
     args = ap.parse_args()
@@ -74,8 +77,15 @@ def main():
     beta = cfg.beta if cfg.beta is not None else 0.0
     stream = torch.cuda.current_stream()
 
+    flags = {"default": None, "warmup": ss.STEP_WARMUP, "sum": ss.STEP_SUM_UPDATE,
+             "sum_out": ss.STEP_SUM_UPDATE}[args.variant]
+    sums = torch.empty(d, dtype=torch.int8, device=dev) if args.variant == "sum_out" else None
+
     def step():
-        ss.signum_vote_step(g, m, beta, cfg.delta, x, voted, None, stream=stream)
+        if flags is None:
+            ss.signum_vote_step(g, m, beta, cfg.delta, x, voted, None, stream=stream)
+        else:
+            ss.signum_vote_step_ex(g, m, beta, cfg.delta, x, voted, None, sums, flags, stream=stream)
 
     for _ in range(args.warmup):
         step()
@@ -97,7 +107,7 @@ def main():
     kernel_ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
     avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
 
-    bytes_per_launch = algorithmic_bytes_per_coordinate(cfg) * d
+    bytes_per_launch = (algorithmic_bytes_per_coordinate(cfg) + (1 if sums is not None else 0)) * d
     achieved = bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
 
     extra = {"kernel_ms_min": kernel_ms[0], "kernel_ms_median": kernel_ms[len(kernel_ms) // 2],
@@ -136,7 +146,7 @@ def main():
     del packed, dst, src
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and flags is None:
         cpu = cpu_baseline(cfg, g, args.cpu_seconds)
 
     out = {
@@ -152,10 +162,11 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: d=%d %s gradients, M=%d workers, beta=%s, delta=%g, fused ss_signum_vote_step"
-                               % (cfg.name, d, cfg.grad_dtype, M, cfg.beta, cfg.delta)},
+        "config": {"workload": "%s: d=%d %s gradients, M=%d workers, beta=%s, delta=%g, fused ss_signum_vote_step%s"
+                               % (cfg.name, d, cfg.grad_dtype, M, cfg.beta, cfg.delta,
+                                  "" if flags is None else "_ex variant=" + args.variant)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic() if args.workload == "C3" else None},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic() if (args.workload == "C3" and flags is None) else None},
         "cpu_baseline": cpu,
         "extra": extra,
     }

@@ -123,6 +123,64 @@ int ss_signum_vote_step(const void *const *g, ss_dtype gdt, float *const *m,
                         uint32_t *voted, uint32_t *const *packed_out, size_t d,
                         void *hip_stream);
 
+/* ---- variants of the step that the paper describes besides Algorithms 1-3 ---- */
+
+typedef enum {
+    SS_STEP_DEFAULT = 0,
+    SS_STEP_WARMUP = 1,    /* Theorem 3: during the first C(beta) iterations every worker votes with
+                              sign(g_w) while its momentum is still updated as in Algorithm 2 */
+    SS_STEP_SUM_UPDATE = 2 /* Section 4, scheme "(good)": x <- x - delta * sum_w s_w (rounded as
+                              fl(x - fl(delta * S)), S converted to fp32 exactly) instead of
+                              x <- x - delta * sign(sum_w s_w) */
+} ss_step_flags;
+
+/*
+ * Theorem 3's warm-up length: the smallest positive integer C with
+ * (C/2) beta^C <= 1/((1 - beta^2)(C + 1)) and beta^(C+1) <= 1/2, evaluated in
+ * double precision (beta^C by repeated multiplication).  Host only, launches
+ * nothing.  54 for beta = 0.9.  SS_ERR_ARG unless 0 < beta < 1.
+ */
+long ss_warmup_length(float beta);
+
+/*
+ * One worker's half of a warm-up iteration (Theorem 3): m <- beta m + (1-beta) g
+ * as in ss_signum_pack, but packed <- bits of sign(g).  m == NULL: same as
+ * ss_signum_pack without momentum.  Arguments as for ss_signum_pack.
+ */
+int ss_signum_pack_warmup(const void *g, ss_dtype gdt, float *m, float beta,
+                          uint32_t *packed, size_t d, void *hip_stream);
+
+/*
+ * Section 4 "(good)", server side: sums_i <- sum_w s_w,i (each s = +-1, so
+ * |sums_i| <= M and sums_i = M mod 2).
+ *   packed  in   host array of M device pointers, ss_packed_bytes(d) bytes each
+ *   sums    out  d x int8, 16-byte aligned
+ */
+int ss_vote_sum(const uint32_t *const *packed, int M, int8_t *sums, size_t d,
+                void *hip_stream);
+
+/*
+ * Section 4 "(good)", worker side: x_i <- fl(x_i - fl(delta * sums_i)).
+ *   x     i/o  d x fp32
+ *   sums  in   d x int8, 16-byte aligned
+ */
+int ss_sum_apply(float *x, const int8_t *sums, float delta, size_t d,
+                 void *hip_stream);
+
+/*
+ * ss_signum_vote_step with the variants selected by `flags` (an OR of
+ * ss_step_flags; unknown bits: SS_ERR_ARG).  `voted` always receives the bits of
+ * sign(sum_w s_w).
+ *   sums_out  out  NULL, or d x int8 (16-byte aligned): sum_w s_w per coordinate
+ * Everything else as for ss_signum_vote_step, which is this call with
+ * flags = SS_STEP_DEFAULT and sums_out = NULL.
+ */
+int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m,
+                           int M, float beta, float delta, float *x,
+                           uint32_t *voted, uint32_t *const *packed_out,
+                           int8_t *sums_out, size_t d, unsigned flags,
+                           void *hip_stream);
+
 /* the hipError_t (as int) behind this thread's most recent SS_ERR_HIP; 0 if none */
 int ss_last_hip_error(void);
 

@@ -7,7 +7,8 @@ kernels.  torch is used for device memory and the current stream.  There is
 no CPU fallback: if the built library is missing, every call raises.
 """
 from .binding import (  # noqa: F401
-    BF16, F32, MAX_WORKERS, SignSGDError, last_hip_error, library_path, load_library,
-    majority_vote, new_bits, packed_bytes, packed_words, sign_apply, signum_pack,
-    signum_vote_step, stream_copy,
+    BF16, F32, MAX_WORKERS, STEP_DEFAULT, STEP_SUM_UPDATE, STEP_WARMUP, SignSGDError,
+    last_hip_error, library_path, load_library, majority_vote, new_bits, packed_bytes,
+    packed_words, sign_apply, signum_pack, signum_pack_warmup, signum_vote_step,
+    signum_vote_step_ex, stream_copy, sum_apply, vote_sum, warmup_length,
 )

@@ -51,8 +51,15 @@ def load_library():
         L.ss_sign_apply.argtypes = [vp, vp, f32, sz, vp]
         L.ss_signum_vote_step.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, sz, vp]
         L.ss_stream_copy.argtypes = [vp, vp, sz, vp]
+        L.ss_warmup_length.restype = ctypes.c_long
+        L.ss_warmup_length.argtypes = [f32]
+        L.ss_signum_pack_warmup.argtypes = [vp, i32, vp, f32, vp, sz, vp]
+        L.ss_vote_sum.argtypes = [vp, i32, vp, sz, vp]
+        L.ss_sum_apply.argtypes = [vp, vp, f32, sz, vp]
+        L.ss_signum_vote_step_ex.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, vp, sz, ctypes.c_uint, vp]
         for name in ("ss_signum_pack", "ss_majority_vote", "ss_sign_apply", "ss_signum_vote_step",
-                     "ss_stream_copy"):
+                     "ss_stream_copy", "ss_signum_pack_warmup", "ss_vote_sum", "ss_sum_apply",
+                     "ss_signum_vote_step_ex"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -111,16 +118,53 @@ def _check(call, status):
 _BITS = (torch.int32, torch.uint32) if hasattr(torch, "uint32") else (torch.int32,)
 
 
-def signum_pack(g, m, beta, packed, d=None, stream=None):
-    """ss_signum_pack: m <- beta m + (1-beta) g; packed <- bits of sign(m)
-    (m None: bits of sign(g))."""
+def _signum_pack(name, g, m, beta, packed, d, stream):
     L = load_library()
     d = g.numel() if d is None else d
     gp = _dev(g, (torch.float32, torch.bfloat16), d, "g")
     mp = _dev(m, torch.float32, d, "m") if m is not None else None
     pp = _dev(packed, _BITS, L.ss_packed_bytes(d) // 4, "packed")
-    _check("ss_signum_pack", L.ss_signum_pack(gp, _grad_dtype(g), mp, beta, pp, d, _stream(stream)))
+    _check(name, getattr(L, name)(gp, _grad_dtype(g), mp, beta, pp, d, _stream(stream)))
     return packed
+
+
+def signum_pack(g, m, beta, packed, d=None, stream=None):
+    """ss_signum_pack: m <- beta m + (1-beta) g; packed <- bits of sign(m)
+    (m None: bits of sign(g))."""
+    return _signum_pack("ss_signum_pack", g, m, beta, packed, d, stream)
+
+
+def signum_pack_warmup(g, m, beta, packed, d=None, stream=None):
+    """ss_signum_pack_warmup: m updated as above, packed <- bits of sign(g)"""
+    return _signum_pack("ss_signum_pack_warmup", g, m, beta, packed, d, stream)
+
+
+def warmup_length(beta):
+    """ss_warmup_length: Theorem 3's C(beta)"""
+    c = load_library().ss_warmup_length(beta)
+    if c < 0:
+        raise SignSGDError("ss_warmup_length", c)
+    return c
+
+
+def vote_sum(packed, sums, d, stream=None):
+    """ss_vote_sum: sums <- per-coordinate sum of the workers' signs (int8)"""
+    L = load_library()
+    n = L.ss_packed_bytes(d) // 4
+    ptrs = [_dev(p, _BITS, n, "packed[%d]" % i) for i, p in enumerate(packed)]
+    sp = _dev(sums, torch.int8, d, "sums")
+    _check("ss_vote_sum", L.ss_vote_sum(_ptr_array(ptrs), len(ptrs), sp, d, _stream(stream)))
+    return sums
+
+
+def sum_apply(x, sums, delta, d=None, stream=None):
+    """ss_sum_apply: x <- x - delta * sums"""
+    L = load_library()
+    d = x.numel() if d is None else d
+    xp = _dev(x, torch.float32, d, "x")
+    sp = _dev(sums, torch.int8, d, "sums")
+    _check("ss_sum_apply", L.ss_sum_apply(xp, sp, delta, d, _stream(stream)))
+    return x
 
 
 def majority_vote(packed, voted, d, stream=None):
@@ -143,9 +187,20 @@ def sign_apply(x, bits, delta, d=None, stream=None):
     return x
 
 
+STEP_DEFAULT = 0
+STEP_WARMUP = 1
+STEP_SUM_UPDATE = 2
+
+
 def signum_vote_step(g, m, beta, delta, x, voted, packed_out=None, d=None, stream=None):
     """ss_signum_vote_step: the whole step for M = len(g) workers in one pass.
     g: list of gradients; m: list of momentum buffers or None."""
+    return signum_vote_step_ex(g, m, beta, delta, x, voted, packed_out, None, None, d, stream)
+
+
+def signum_vote_step_ex(g, m, beta, delta, x, voted, packed_out=None, sums_out=None, flags=None, d=None,
+                        stream=None):
+    """ss_signum_vote_step_ex (flags None: the plain ss_signum_vote_step entry point)"""
     L = load_library()
     M = len(g)
     d = x.numel() if d is None else d
@@ -159,9 +214,16 @@ def signum_vote_step(g, m, beta, delta, x, voted, packed_out=None, d=None, strea
         raise ValueError("g, m and packed_out must have one entry per worker")
     xp = _dev(x, torch.float32, d, "x")
     vp = _dev(voted, _BITS, n, "voted")
-    _check("ss_signum_vote_step", L.ss_signum_vote_step(
-        _ptr_array(gp), gdt, _ptr_array(mp) if mp is not None else None, M, beta, delta, xp, vp,
-        _ptr_array(pp) if pp is not None else None, d, _stream(stream)))
+    g_arr = _ptr_array(gp)
+    m_arr = _ptr_array(mp) if mp is not None else None
+    p_arr = _ptr_array(pp) if pp is not None else None
+    if flags is None and sums_out is None:
+        _check("ss_signum_vote_step", L.ss_signum_vote_step(
+            g_arr, gdt, m_arr, M, beta, delta, xp, vp, p_arr, d, _stream(stream)))
+    else:
+        sp = _dev(sums_out, torch.int8, d, "sums_out") if sums_out is not None else None
+        _check("ss_signum_vote_step_ex", L.ss_signum_vote_step_ex(
+            g_arr, gdt, m_arr, M, beta, delta, xp, vp, p_arr, sp, d, int(flags or 0), _stream(stream)))
     return voted
 
 

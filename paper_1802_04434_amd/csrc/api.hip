@@ -81,6 +81,9 @@ void fill_step_args(ss::StepArgs<NPTR> &a, int M, const void *const *g, float *c
     a.delta = delta;
     a.M = M;
     a.write_packed = packed != nullptr;
+    a.warmup = 0;
+    a.sum_update = 0;
+    a.sums = nullptr;
     a.d = d;
 }
 
@@ -97,12 +100,21 @@ int launch_step_shape(ss::StepArgs<NPTR> &a, size_t d, hipStream_t stream) {
 }
 
 // MT > 0: M fixed at compile time; MT == 0: any M up to SS_MAX_WORKERS
+// what distinguishes the variants of the step (see ss_step_flags)
+struct StepVariant {
+    unsigned flags;
+    int8_t *sums;
+};
+
 template <int MT, bool HAS_M, bool VOTE, typename G>
 int launch_step_m(int M, const void *const *g, float *const *m, uint32_t *const *packed, float beta, float delta,
-                  float *x, uint32_t *voted, size_t d, hipStream_t stream) {
+                  float *x, uint32_t *voted, StepVariant var, size_t d, hipStream_t stream) {
     constexpr int NPTR = MT > 0 ? MT : SS_MAX_WORKERS;
     ss::StepArgs<NPTR> a;
     fill_step_args<NPTR>(a, M, g, HAS_M ? m : nullptr, packed, beta, delta, x, voted, d);
+    a.warmup = (var.flags & SS_STEP_WARMUP) ? 1 : 0;
+    a.sum_update = (var.flags & SS_STEP_SUM_UPDATE) ? 1 : 0;
+    a.sums = var.sums;
     if constexpr (MT == 1) {
         // a single worker is two or three streams whatever the shape: no cap needed
         constexpr int R = VOTE ? 2 : 4;
@@ -118,13 +130,13 @@ int launch_step_m(int M, const void *const *g, float *const *m, uint32_t *const 
 
 template <bool HAS_M, typename G>
 int launch_step(int M, const void *const *g, float *const *m, uint32_t *const *packed, float beta,
-                float delta, float *x, uint32_t *voted, size_t d, hipStream_t stream) {
+                float delta, float *x, uint32_t *voted, StepVariant var, size_t d, hipStream_t stream) {
 #define SS_CASE(n) \
-    case n: return launch_step_m<n, HAS_M, true, G>(M, g, m, packed, beta, delta, x, voted, d, stream)
+    case n: return launch_step_m<n, HAS_M, true, G>(M, g, m, packed, beta, delta, x, voted, var, d, stream)
     switch (M) {
         SS_CASE(1); SS_CASE(2); SS_CASE(3); SS_CASE(4); SS_CASE(5); SS_CASE(6); SS_CASE(7); SS_CASE(8);
         SS_CASE(16);
-        default: return launch_step_m<0, HAS_M, true, G>(M, g, m, packed, beta, delta, x, voted, d, stream);
+        default: return launch_step_m<0, HAS_M, true, G>(M, g, m, packed, beta, delta, x, voted, var, d, stream);
     }
 #undef SS_CASE
 }
@@ -166,8 +178,8 @@ size_t ss_packed_bytes(size_t d) { return (ss_packed_words(d) * 4 + 15) / 16 * 1
 
 int ss_last_hip_error(void) { return g_last_hip_error; }
 
-int ss_signum_pack(const void *g, ss_dtype gdt, float *m, float beta, uint32_t *packed, size_t d,
-                   void *hip_stream) {
+static int signum_pack_impl(const void *g, ss_dtype gdt, float *m, float beta, uint32_t *packed, size_t d,
+                            unsigned flags, void *hip_stream) {
     if (gdt != SS_F32 && gdt != SS_BF16) return SS_ERR_DTYPE;
     if (d == 0) return SS_OK;
     if (!g || !packed) return SS_ERR_NULL;
@@ -176,14 +188,39 @@ int ss_signum_pack(const void *g, ss_dtype gdt, float *m, float beta, uint32_t *
     const void *gs[1] = {g};
     float *ms[1] = {m};
     uint32_t *ps[1] = {packed};
+    const StepVariant var{flags, nullptr};
     if (m) {
         if (gdt == SS_F32)
-            return launch_step_m<1, true, false, ss::F32Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
-        return launch_step_m<1, true, false, ss::Bf16Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+            return launch_step_m<1, true, false, ss::F32Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, var, d, stream);
+        return launch_step_m<1, true, false, ss::Bf16Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, var, d, stream);
     }
     if (gdt == SS_F32)
-        return launch_step_m<1, false, false, ss::F32Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
-    return launch_step_m<1, false, false, ss::Bf16Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, d, stream);
+        return launch_step_m<1, false, false, ss::F32Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, var, d, stream);
+    return launch_step_m<1, false, false, ss::Bf16Grad>(1, gs, ms, ps, beta, 0.0f, nullptr, nullptr, var, d, stream);
+}
+
+int ss_signum_pack(const void *g, ss_dtype gdt, float *m, float beta, uint32_t *packed, size_t d,
+                   void *hip_stream) {
+    return signum_pack_impl(g, gdt, m, beta, packed, d, SS_STEP_DEFAULT, hip_stream);
+}
+
+int ss_signum_pack_warmup(const void *g, ss_dtype gdt, float *m, float beta, uint32_t *packed, size_t d,
+                          void *hip_stream) {
+    return signum_pack_impl(g, gdt, m, beta, packed, d, SS_STEP_WARMUP, hip_stream);
+}
+
+long ss_warmup_length(float beta_f) {
+    const double beta = (double)beta_f;
+    if (!(beta > 0.0 && beta < 1.0)) return SS_ERR_ARG;
+    // smallest C >= 1 with (C/2) beta^C (C+1) (1 - beta^2) <= 1 and beta^(C+1) <= 1/2
+    double beta_to_c = 1.0;
+    for (long c = 1; c <= 1000000000L; ++c) {
+        beta_to_c *= beta;
+        const bool bias_settled = 0.5 * (double)c * beta_to_c <= 1.0 / ((1.0 - beta * beta) * ((double)c + 1.0));
+        const bool decayed = beta_to_c * beta <= 0.5;
+        if (bias_settled && decayed) return c;
+    }
+    return SS_ERR_ARG;
 }
 
 int ss_majority_vote(const uint32_t *const *packed, int M, uint32_t *voted, size_t d, void *hip_stream) {
@@ -224,10 +261,12 @@ int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d, void *h
     return launch_status();
 }
 
-int ss_signum_vote_step(const void *const *g, ss_dtype gdt, float *const *m, int M, float beta, float delta,
-                        float *x, uint32_t *voted, uint32_t *const *packed_out, size_t d, void *hip_stream) {
+int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m, int M, float beta, float delta,
+                           float *x, uint32_t *voted, uint32_t *const *packed_out, int8_t *sums_out, size_t d,
+                           unsigned flags, void *hip_stream) {
     if (M < 1 || M > SS_MAX_WORKERS) return SS_ERR_BAD_M;
     if (gdt != SS_F32 && gdt != SS_BF16) return SS_ERR_DTYPE;
+    if (flags & ~(unsigned)(SS_STEP_WARMUP | SS_STEP_SUM_UPDATE)) return SS_ERR_ARG;
     if (d == 0) return SS_OK;
     if (!g || !x || !voted) return SS_ERR_NULL;
     for (int w = 0; w < M; ++w) {
@@ -235,21 +274,67 @@ int ss_signum_vote_step(const void *const *g, ss_dtype gdt, float *const *m, int
         if (m && !m[w]) return SS_ERR_NULL;
         if (packed_out && !packed_out[w]) return SS_ERR_NULL;
     }
-    if (!aligned16(x) || !aligned16(voted)) return SS_ERR_ALIGN;
+    if (!aligned16(x) || !aligned16(voted) || !aligned16(sums_out)) return SS_ERR_ALIGN;
     for (int w = 0; w < M; ++w) {
         if (!aligned16(g[w])) return SS_ERR_ALIGN;
         if (m && !aligned16(m[w])) return SS_ERR_ALIGN;
         if (packed_out && !aligned16(packed_out[w])) return SS_ERR_ALIGN;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const StepVariant var{flags, sums_out};
     if (m) {
         if (gdt == SS_F32)
-            return launch_step<true, ss::F32Grad>(M, g, m, packed_out, beta, delta, x, voted, d, stream);
-        return launch_step<true, ss::Bf16Grad>(M, g, m, packed_out, beta, delta, x, voted, d, stream);
+            return launch_step<true, ss::F32Grad>(M, g, m, packed_out, beta, delta, x, voted, var, d, stream);
+        return launch_step<true, ss::Bf16Grad>(M, g, m, packed_out, beta, delta, x, voted, var, d, stream);
     }
     if (gdt == SS_F32)
-        return launch_step<false, ss::F32Grad>(M, g, m, packed_out, beta, delta, x, voted, d, stream);
-    return launch_step<false, ss::Bf16Grad>(M, g, m, packed_out, beta, delta, x, voted, d, stream);
+        return launch_step<false, ss::F32Grad>(M, g, m, packed_out, beta, delta, x, voted, var, d, stream);
+    return launch_step<false, ss::Bf16Grad>(M, g, m, packed_out, beta, delta, x, voted, var, d, stream);
+}
+
+int ss_signum_vote_step(const void *const *g, ss_dtype gdt, float *const *m, int M, float beta, float delta,
+                        float *x, uint32_t *voted, uint32_t *const *packed_out, size_t d, void *hip_stream) {
+    return ss_signum_vote_step_ex(g, gdt, m, M, beta, delta, x, voted, packed_out, nullptr, d, SS_STEP_DEFAULT,
+                                  hip_stream);
+}
+
+int ss_vote_sum(const uint32_t *const *packed, int M, int8_t *sums, size_t d, void *hip_stream) {
+    if (M < 1 || M > SS_MAX_WORKERS) return SS_ERR_BAD_M;
+    if (d == 0) return SS_OK;
+    if (!packed || !sums) return SS_ERR_NULL;
+    for (int w = 0; w < M; ++w)
+        if (!packed[w]) return SS_ERR_NULL;
+    if (!aligned16(sums)) return SS_ERR_ALIGN;
+    for (int w = 0; w < M; ++w)
+        if (!aligned16(packed[w])) return SS_ERR_ALIGN;
+    ss::VoteSumArgs a;
+    for (int w = 0; w < SS_MAX_WORKERS; ++w) a.packed[w] = w < M ? packed[w] : nullptr;
+    a.sums = sums;
+    a.M = M;
+    a.d = d;
+    a.n_halves = (d + 15) / 16;
+    const size_t grid = (a.n_halves + ss::kBlock - 1) / ss::kBlock;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::vote_sum_kernel<<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
+    return launch_status();
+}
+
+int ss_sum_apply(float *x, const int8_t *sums, float delta, size_t d, void *hip_stream) {
+    if (d == 0) return SS_OK;
+    if (!x || !sums) return SS_ERR_NULL;
+    if (!aligned16(x) || !aligned16(sums)) return SS_ERR_ALIGN;
+    constexpr int R = 4;
+    const Tiling t = make_tiling(d, R, false);
+    ss::SumApplyArgs a;
+    a.x = x;
+    a.sums = sums;
+    a.delta = delta;
+    a.d = d;
+    a.n_tiles = t.n_tiles;
+    const size_t grid = t.n_tiles + t.tail_blocks;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::sum_apply_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
+    return launch_status();
 }
 
 int ss_stream_copy(void *dst, const void *src, size_t nbytes, void *hip_stream) {

@@ -38,6 +38,9 @@ struct StepArgs {
     float beta, omb, delta;
     int M;               // number of workers in use (<= NPTR)
     int write_packed;    // per-worker bits wanted
+    int warmup;          // Theorem 3 warm-up: signs come from g while m is still updated
+    int sum_update;      // Section 4 "(good)": x <- x - delta * (sum of signs) instead of its sign
+    int8_t *sums;        // VOTE only, may be NULL: per-coordinate sum of signs
     size_t d;            // coordinates
     size_t n_tiles;      // blocks on the vector path (R rows of kRowCoords coordinates each)
     size_t words_total;  // words of a packed buffer including zero padding
@@ -55,6 +58,24 @@ __device__ __forceinline__ uint32_t vote_nibble(uint32_t counts, int T) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) nib |= (((counts >> (8 * k)) & 0xFFu) >= (uint32_t)T ? 1u : 0u) << k;
     return nib;
+}
+
+// the four sums of signs of a quad, S = M - 2 * (count of "-"), as four int8
+// in one word.  Biasing every byte by 128 keeps each byte's arithmetic inside
+// the byte; flipping bit 7 afterwards removes the bias modulo 256.
+__device__ __forceinline__ uint32_t sums_word(uint32_t counts, int M) {
+    return ((0x80808080u + (uint32_t)M * 0x01010101u) - 2u * counts) ^ 0x80808080u;
+}
+
+// Section 4 "(good)" for one coordinate: x - delta * S, product and
+// difference each rounded (the file is compiled with contraction off)
+__device__ __forceinline__ float step_sum(float x, float delta, int S) {
+    const float t = delta * (float)S;
+    return x - t;
+}
+
+__device__ __forceinline__ int sum_at(uint32_t counts, int k, int M) {
+    return M - 2 * (int)((counts >> (8 * k)) & 0xFFu);
 }
 
 // Occupancy governor: a block that declares BYTES of LDS keeps other blocks
@@ -121,7 +142,8 @@ __global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
                             v.w = momentum(a.beta, a.omb, m0.w, v.w);
                             st_stream(reinterpret_cast<f32x4 *>(a.p.m[w0 + j]) + q[r], v);
                         }
-                        const uint32_t nib = neg_nibble(v);
+                        // Algorithm 2 votes with sign(m); a warm-up iteration with sign(g)
+                        const uint32_t nib = neg_nibble((HAS_M && a.warmup) ? gv[r][j] : v);
                         counts[r] += spread_nibble(nib);
                         if (a.write_packed) {
                             const uint32_t word = combine8(nib, lane);
@@ -136,11 +158,19 @@ __global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
             for (int r = 0; r < R; ++r) {
                 const uint32_t nib = vote_nibble(counts[r], T);
                 f32x4 v = xv[r];
-                v.x = step(v.x, a.delta, nib & 1u);
-                v.y = step(v.y, a.delta, nib & 2u);
-                v.z = step(v.z, a.delta, nib & 4u);
-                v.w = step(v.w, a.delta, nib & 8u);
+                if (a.sum_update) {
+                    v.x = step_sum(v.x, a.delta, sum_at(counts[r], 0, M));
+                    v.y = step_sum(v.y, a.delta, sum_at(counts[r], 1, M));
+                    v.z = step_sum(v.z, a.delta, sum_at(counts[r], 2, M));
+                    v.w = step_sum(v.w, a.delta, sum_at(counts[r], 3, M));
+                } else {
+                    v.x = step(v.x, a.delta, nib & 1u);
+                    v.y = step(v.y, a.delta, nib & 2u);
+                    v.z = step(v.z, a.delta, nib & 4u);
+                    v.w = step(v.w, a.delta, nib & 8u);
+                }
                 st_stream(reinterpret_cast<f32x4 *>(a.x) + q[r], v);
+                if (a.sums) reinterpret_cast<uint32_t *>(a.sums)[q[r]] = sums_word(counts[r], M);
                 const uint32_t word = combine8(nib, lane);
                 if ((lane & 7) == 0) a.voted[q[r] >> 3] = word;
             }
@@ -159,10 +189,12 @@ __global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
     for (int w = 0; w < M; ++w) {
         float v = 0.0f;
         if (in) {
-            v = G::load1(a.p.g[w], i);
+            const float gi = G::load1(a.p.g[w], i);
+            v = gi;
             if (HAS_M) {
-                v = momentum(a.beta, a.omb, a.p.m[w][i], v);
+                v = momentum(a.beta, a.omb, a.p.m[w][i], gi);
                 a.p.m[w][i] = v;
+                if (a.warmup) v = gi;
             }
         }
         const bool neg = in && v < 0.0f;
@@ -174,7 +206,10 @@ __global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
     }
     if (VOTE) {
         const bool vneg = in && count >= T;
-        if (in) a.x[i] = step(a.x[i], a.delta, vneg);
+        if (in) {
+            a.x[i] = a.sum_update ? step_sum(a.x[i], a.delta, M - 2 * count) : step(a.x[i], a.delta, vneg);
+            if (a.sums) a.sums[i] = (int8_t)(M - 2 * count);
+        }
         const uint64_t mask = __builtin_amdgcn_ballot_w64(vneg);
         if (writes_word) a.voted[word] = (uint32_t)(lane == 0 ? mask : mask >> 32);
     }

@@ -2,7 +2,7 @@
 // packed sign words and the worker's parameter update from packed bits
 // (arxiv 1802.04434, Algorithm 3; Algorithm 1 when the bits are one worker's).
 #pragma once
-#include "common.hpp"
+#include "step_kernels.hpp"
 
 namespace ss {
 
@@ -183,6 +183,82 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(const ApplyArgs a) {
         const bool neg = (a.bits[i >> 5] >> (i & 31)) & 1u;
         a.x[i] = step(a.x[i], a.delta, neg);
     }
+}
+
+// ------------------------------------------------ "(good)": vote sums ----
+// Section 4's first scheme sends back the sum of the workers' signs instead of
+// its sign.  A lane owns 16 consecutive coordinates (half a packed word) so
+// that its 16 int8 sums leave as one 128-bit store; the count of "-" votes is
+// kept in byte lanes of four registers.
+
+struct VoteSumArgs {
+    const uint32_t *packed[64];
+    int8_t *sums;
+    int M;
+    size_t d;
+    size_t n_halves;   // ceil(d / 16)
+};
+
+__global__ __launch_bounds__(kBlock) void vote_sum_kernel(const VoteSumArgs a) {
+    const size_t h = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (h >= a.n_halves) return;
+    uint32_t counts[4] = {0, 0, 0, 0};
+    const unsigned shift = (unsigned)(h & 1) * 16u;
+    for (int w = 0; w < a.M; ++w) {
+        const uint32_t bits = (a.packed[w][h >> 1] >> shift) & 0xFFFFu;
+#pragma unroll
+        for (int n = 0; n < 4; ++n) counts[n] += spread_nibble((bits >> (4 * n)) & 0xFu);
+    }
+    u32x4 out;
+    out.x = sums_word(counts[0], a.M);
+    out.y = sums_word(counts[1], a.M);
+    out.z = sums_word(counts[2], a.M);
+    out.w = sums_word(counts[3], a.M);
+    const size_t first = h * 16;
+    if (first + 16 <= a.d) {
+        st_stream(reinterpret_cast<u32x4 *>(a.sums + first), out);
+    } else {
+        const uint32_t words[4] = {out.x, out.y, out.z, out.w};
+        for (size_t i = first; i < a.d; ++i)
+            a.sums[i] = (int8_t)(words[(i - first) >> 2] >> (8 * ((i - first) & 3)));
+    }
+}
+
+struct SumApplyArgs {
+    float *x;
+    const int8_t *sums;
+    float delta;
+    size_t d;
+    size_t n_tiles;
+};
+
+template <int R>
+__global__ __launch_bounds__(kBlock) void sum_apply_kernel(const SumApplyArgs a) {
+    const int tid = threadIdx.x;
+    const size_t tile = blockIdx.x;
+    if (tile < a.n_tiles) {
+        size_t q[R];
+        f32x4 xv[R];
+        uint32_t sw[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            q[r] = (tile * R + r) * kBlock + tid;
+            xv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.x) + q[r]);
+            sw[r] = ld_stream(reinterpret_cast<const uint32_t *>(a.sums) + q[r]);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            f32x4 v = xv[r];
+            v.x = step_sum(v.x, a.delta, (int)(int8_t)(sw[r] & 0xFFu));
+            v.y = step_sum(v.y, a.delta, (int)(int8_t)((sw[r] >> 8) & 0xFFu));
+            v.z = step_sum(v.z, a.delta, (int)(int8_t)((sw[r] >> 16) & 0xFFu));
+            v.w = step_sum(v.w, a.delta, (int)(int8_t)(sw[r] >> 24));
+            st_stream(reinterpret_cast<f32x4 *>(a.x) + q[r], v);
+        }
+        return;
+    }
+    const size_t i = a.n_tiles * (size_t)(R * kRowCoords) + (tile - a.n_tiles) * kBlock + tid;
+    if (i < a.d) a.x[i] = step_sum(a.x[i], a.delta, (int)a.sums[i]);
 }
 
 // ---------------------------------------------------------------- copy ----

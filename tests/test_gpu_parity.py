@@ -303,9 +303,9 @@ def test_checkpoint_resume_is_bit_identical(ss):
 
 @pytest.mark.parametrize("M,dtype,momentum", [(2, "f32", True), (3, "bf16", True), (4, "f32", False),
                                               (9, "f32", True), (11, "bf16", False)])
-def test_fused_step_large_d_worker_major_path(ss, oracle, M, dtype, momentum):
-    # large enough that the library sweeps worker by worker with resident
-    # blocks (counts in LDS); ragged so that the scalar tail runs as well
+def test_fused_step_large_d_streaming_shape(ss, oracle, M, dtype, momentum):
+    # large enough for the one-worker-at-a-time launch shape with capped
+    # occupancy; ragged so that the scalar tail runs as well
     d = 9_000_000 + 1234 + 19
     cfg = synth.Config("large", 40 + M, d, M, dtype, 0.9 if momentum else None, 1e-4, 2, "normal", 0.1, 0.5)
     m = [np.zeros(d, np.float32) for _ in range(M)] if momentum else None

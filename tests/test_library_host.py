@@ -96,3 +96,32 @@ def test_product_package_does_not_reach_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower().replace("no fallback", ""), f
                 assert "sso_" not in text, f
+
+
+def test_warmup_length_matches_the_paper_and_the_oracle(lib, oracle):
+    lib.ss_warmup_length.restype = ctypes.c_long
+    lib.ss_warmup_length.argtypes = [ctypes.c_float]
+    assert lib.ss_warmup_length(0.9) == 54                  # Theorem 3: "for beta = 0.9 we have C = 54"
+    for beta in (0.1, 0.5, 0.75, 0.8, 0.9, 0.95, 0.99, 0.999):
+        assert lib.ss_warmup_length(beta) == oracle.warmup_length(beta)
+    for beta in (0.0, 1.0, -1.0, 2.0, float("nan")):
+        assert lib.ss_warmup_length(beta) == -5
+
+
+def test_variant_entry_points_validate_arguments(lib):
+    a = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    one = (ctypes.c_void_p * 1)(0x1000)
+    step_ex = lib.ss_signum_vote_step_ex
+    assert step_ex(one, 0, None, 1, 0.9, 0.1, a, a, None, None, 8, 4, None) == -5      # unknown flag
+    assert step_ex(one, 0, None, 1, 0.9, 0.1, a, a, None, odd, 8, 2, None) == -3
+    assert step_ex(one, 0, None, 0, 0.9, 0.1, a, a, None, None, 8, 0, None) == -2
+    assert step_ex(None, 0, None, 1, 0.9, 0.1, a, a, None, None, 0, 3, None) == 0
+    assert lib.ss_vote_sum(one, 1, None, 8, None) == -1
+    assert lib.ss_vote_sum(one, 1, odd, 8, None) == -3
+    assert lib.ss_vote_sum(one, 65, a, 8, None) == -2
+    assert lib.ss_vote_sum(None, 1, None, 0, None) == 0
+    assert lib.ss_sum_apply(None, a, 0.1, 8, None) == -1
+    assert lib.ss_sum_apply(a, odd, 0.1, 8, None) == -3
+    assert lib.ss_signum_pack_warmup(a, 5, None, 0.9, a, 8, None) == -4
+    assert lib.ss_signum_pack_warmup(None, 0, None, 0.9, a, 8, None) == -1
