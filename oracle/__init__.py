@@ -40,6 +40,9 @@ def lib():
         L.sso_signum_pack_warmup.argtypes = [vp, i32, vp, f32, vp, sz]
         L.sso_sum_apply.argtypes = [vp, vp, f32, sz]
         L.sso_signum_vote_step_ex.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, vp, sz, ctypes.c_uint]
+        L.sso_density.argtypes = [vp, sz, vp]
+        L.sso_welford_update.argtypes = [vp, i32, vp, vp, ctypes.c_uint64, sz]
+        L.sso_welford_sigma.argtypes = [vp, ctypes.c_uint64, vp, sz]
         _lib = L
     return _lib
 
@@ -198,3 +201,26 @@ def signum_vote_step_ex(g, m, beta, delta, x, flags, d=None):
                                          _ptr_array(packed), _ptr(sums), d, int(flags)),
            "sso_signum_vote_step_ex")
     return voted, packed, sums
+
+
+def density(v):
+    """(|v|_1, |v|_2^2, phi(v)) of equation (1)"""
+    _need(v, np.float32, len(v), "v")
+    out = np.zeros(3, dtype=np.float64)
+    _check(lib().sso_density(_ptr(v) if len(v) else None, len(v), _ptr(out)), "sso_density")
+    return tuple(float(t) for t in out)
+
+
+def welford_update(g, mean, m2, n):
+    d = len(mean)
+    gdt = _grad_dtype(g)
+    _need(g, g.dtype, d, "g")
+    _need(mean, np.float32, d, "mean")
+    _need(m2, np.float32, d, "m2")
+    _check(lib().sso_welford_update(_ptr(g), gdt, _ptr(mean), _ptr(m2), int(n), d), "sso_welford_update")
+
+
+def welford_sigma(m2, n):
+    sigma = np.empty_like(m2)
+    _check(lib().sso_welford_sigma(_ptr(m2), int(n), _ptr(sigma), len(m2)), "sso_welford_sigma")
+    return sigma

@@ -23,6 +23,10 @@
  *   sso_signum_pack_warmup  Theorem 3's warm-up iteration: momentum is
  *                     accumulated as usual, the sign is taken from the gradient.
  *   sso_signum_vote_step_ex  the whole step with either or both variants.
+ *   sso_density       equation (1): phi(v) = |v|_1^2 / (d |v|_2^2).
+ *   sso_welford_update, sso_welford_sigma  the single-pass mean / variance of a
+ *                     sequence of stochastic gradients that Section 3 uses to
+ *                     measure gradient and noise density (Welford's algorithm).
  *
  * Readings the paper leaves open, fixed here:
  *   sign(v) = -1 if v < 0, else +1.  Zero (either sign of zero) is "+".
@@ -39,6 +43,14 @@
  *   bf16 gradients are widened to fp32 exactly before use.
  *   "(good)" update: x <- fl(x - fl(delta * S)) with the integer sum S
  *     converted to fp32 exactly; with momentum, S sums sign(m_m).
+ *   density: every term (|v_i|, v_i^2) is exact in double; the two sums are
+ *     accumulated in long double, so the oracle's own rounding is negligible
+ *     next to the tolerance the GPU's fp64 sums are held to.
+ *   Welford, per coordinate and in fp32, n = index of this gradient (1-based):
+ *     delta = g - mean; mean <- mean + delta / n; m2 <- m2 + delta * (g - mean)
+ *     each operation rounded once (division and square root correctly
+ *     rounded), n converted to fp32 (exact below 2^24);
+ *     sigma = sqrt(m2 / n): the population standard deviation over the pass.
  *   C(beta) is evaluated in double precision with beta^C built by repeated
  *     multiplication; the smallest positive integer meeting both conditions
  *     of Theorem 3 is returned, exactly as the theorem states it.
@@ -359,4 +371,63 @@ int sso_signum_vote_step_ex(const void *const *g, int gdt, float *const *m,
     free(own);
     free(signs);
     return rc;
+}
+
+/* ---- gradient statistics (Section 3, equation (1) and Figure 1) ---- */
+
+/* out[0] = |v|_1, out[1] = |v|_2^2, out[2] = phi(v) = |v|_1^2 / (d |v|_2^2) */
+int sso_density(const float *v, size_t d, double *out)
+{
+    if (!out) return SSO_ERR_NULL;
+    if (d == 0) {
+        out[0] = out[1] = 0.0;
+        out[2] = 0.0;
+        return SSO_OK;
+    }
+    if (!v) return SSO_ERR_NULL;
+    long double l1 = 0.0L, l2sq = 0.0L;
+    for (size_t i = 0; i < d; ++i) {
+        double a = v[i] < 0.0f ? -(double)v[i] : (double)v[i];
+        l1 += a;
+        l2sq += a * a; /* exact: 24-bit significands */
+    }
+    out[0] = (double)l1;
+    out[1] = (double)l2sq;
+    out[2] = l2sq > 0.0L ? (double)(l1 * l1 / ((long double)d * l2sq)) : 0.0;
+    return SSO_OK;
+}
+
+/* Welford's update with the n-th gradient (n >= 1) */
+int sso_welford_update(const void *g, int gdt, float *mean, float *m2,
+                       uint64_t n, size_t d)
+{
+    if (gdt != SSO_F32 && gdt != SSO_BF16) return SSO_ERR_DTYPE;
+    if (n < 1) return SSO_ERR_ARG;
+    if (d == 0) return SSO_OK;
+    if (!g || !mean || !m2) return SSO_ERR_NULL;
+    const float nf = (float)n;
+    for (size_t i = 0; i < d; ++i) {
+        float gi = grad_at(g, gdt, i);
+        float delta = gi - mean[i];
+        float q = delta / nf;
+        mean[i] = mean[i] + q;
+        float delta2 = gi - mean[i];
+        float p = delta * delta2;
+        m2[i] = m2[i] + p;
+    }
+    return SSO_OK;
+}
+
+/* sigma_i = sqrt(m2_i / n) */
+int sso_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d)
+{
+    if (n < 1) return SSO_ERR_ARG;
+    if (d == 0) return SSO_OK;
+    if (!m2 || !sigma) return SSO_ERR_NULL;
+    const float nf = (float)n;
+    for (size_t i = 0; i < d; ++i) {
+        float var = m2[i] / nf;
+        sigma[i] = __builtin_sqrtf(var);
+    }
+    return SSO_OK;
 }
