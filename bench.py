@@ -47,9 +47,10 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--variant", default="default", choices=["default", "warmup", "sum", "sum_out"],
+    ap.add_argument("--variant", default="default", choices=["default", "warmup", "sum", "sum_out", "welford", "density"],
                     help="default: Algorithms 2+3; warmup: Theorem 3 warm-up iteration; sum: '(good)' "
-                         "update; sum_out: '(good)' update that also writes the int8 vote sums")
+                         "update; sum_out: '(good)' update that also writes the int8 vote sums; "
+                         "welford / density: the gradient-statistics kernels of Section 3 on one worker's gradient")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target length of the oracle timing")
     args = ap.parse_args()
@@ -78,11 +79,20 @@ def main():
     stream = torch.cuda.current_stream()
 
     flags = {"default": None, "warmup": ss.STEP_WARMUP, "sum": ss.STEP_SUM_UPDATE,
-             "sum_out": ss.STEP_SUM_UPDATE}[args.variant]
+             "sum_out": ss.STEP_SUM_UPDATE, "welford": -1, "density": -1}[args.variant]
     sums = torch.empty(d, dtype=torch.int8, device=dev) if args.variant == "sum_out" else None
+    if args.variant == "welford":
+        w_mean, w_m2 = torch.zeros(d, device=dev), torch.zeros(d, device=dev)
+    if args.variant == "density":
+        phi = torch.zeros(3, dtype=torch.float64, device=dev)
+        g32 = g[0].float()
 
     def step():
-        if flags is None:
+        if args.variant == "welford":
+            ss.welford_update(g[0], w_mean, w_m2, 7, stream=stream)
+        elif args.variant == "density":
+            ss.density(g32, phi, stream=stream)
+        elif flags is None:
             ss.signum_vote_step(g, m, beta, cfg.delta, x, voted, None, stream=stream)
         else:
             ss.signum_vote_step_ex(g, m, beta, cfg.delta, x, voted, None, sums, flags, stream=stream)
@@ -108,10 +118,26 @@ def main():
     avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
 
     bytes_per_launch = (algorithmic_bytes_per_coordinate(cfg) + (1 if sums is not None else 0)) * d
+    if args.variant == "welford":      # read g, mean, m2; write mean, m2
+        bytes_per_launch = ((4 if cfg.grad_dtype == "f32" else 2) + 16) * d
+    if args.variant == "density":      # read v
+        bytes_per_launch = 4 * d
     achieved = bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
 
     extra = {"kernel_ms_min": kernel_ms[0], "kernel_ms_median": kernel_ms[len(kernel_ms) // 2],
              "kernel_ms_avg": avg_kernel_ms, "algorithmic_bytes_per_launch": bytes_per_launch}
+
+    if flags == -1:
+        name = {"welford": "ss_welford_update", "density": "ss_density (2 launches)"}[args.variant]
+        print(json.dumps({
+            "metric": "coordinates/sec for %s, d=%d" % (name, d), "value": d / (wall_ms * 1e-3), "unit": "params/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall_ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "%s on one worker's gradient of %s" % (name, cfg.name)},
+            "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+            "cpu_baseline": None, "extra": extra}), flush=True)
+        return
 
     # context: the three-call path (M packs, vote, apply) and a plain copy
     packed = [ss.new_bits(d, dev) for _ in range(M)]

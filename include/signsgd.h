@@ -181,6 +181,38 @@ int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m,
                            int8_t *sums_out, size_t d, unsigned flags,
                            void *hip_stream);
 
+/* ---- gradient statistics (Section 3: equation (1) and Figure 1) ---- */
+
+/*
+ * Welford's single-pass mean / variance over a sequence of stochastic
+ * gradients, one call per gradient.  Per coordinate, in fp32, every operation
+ * rounded once (division correctly rounded):
+ *     delta = g - mean;  mean <- mean + delta / n;  m2 <- m2 + delta * (g - mean)
+ *   g     in   d elements of type gdt (bf16 widened exactly): the n-th gradient
+ *   mean  i/o  d x fp32, running mean (all zero before the first call)
+ *   m2    i/o  d x fp32, running sum of squared deviations (all zero before the first call)
+ *   n     1-based index of this gradient, at most 2^24 (so that it is exact in fp32)
+ */
+int ss_welford_update(const void *g, ss_dtype gdt, float *mean, float *m2,
+                      uint64_t n, size_t d, void *hip_stream);
+
+/* sigma_i <- sqrt(m2_i / n): the standard deviation over the n gradients seen
+ * (division and square root correctly rounded).  m2, sigma: d x fp32. */
+int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d,
+                     void *hip_stream);
+
+/*
+ * Equation (1): the density phi(v) = |v|_1^2 / (d |v|_2^2) of a vector
+ * (1 for a fully dense vector, 1/d for a one-hot one).
+ *   v    in   d x fp32
+ *   out  out  3 doubles in DEVICE memory, 16-byte aligned:
+ *             out[0] = |v|_1, out[1] = |v|_2^2, out[2] = phi(v) (0 for the zero vector)
+ * The sums are accumulated in fp64 (every term is exact); the order of the
+ * last additions is not fixed, so results may differ between runs in the last
+ * bits (relative error below 1e-12).  Two launches on hip_stream.
+ */
+int ss_density(const float *v, size_t d, double *out, void *hip_stream);
+
 /* the hipError_t (as int) behind this thread's most recent SS_ERR_HIP; 0 if none */
 int ss_last_hip_error(void);
 

@@ -11,4 +11,5 @@ from .binding import (  # noqa: F401
     last_hip_error, library_path, load_library, majority_vote, new_bits, packed_bytes,
     packed_words, sign_apply, signum_pack, signum_pack_warmup, signum_vote_step,
     signum_vote_step_ex, stream_copy, sum_apply, vote_sum, warmup_length,
+    density, welford_sigma, welford_update,
 )

@@ -57,6 +57,11 @@ def load_library():
         L.ss_vote_sum.argtypes = [vp, i32, vp, sz, vp]
         L.ss_sum_apply.argtypes = [vp, vp, f32, sz, vp]
         L.ss_signum_vote_step_ex.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, vp, sz, ctypes.c_uint, vp]
+        L.ss_welford_update.argtypes = [vp, i32, vp, vp, ctypes.c_uint64, sz, vp]
+        L.ss_welford_sigma.argtypes = [vp, ctypes.c_uint64, vp, sz, vp]
+        L.ss_density.argtypes = [vp, sz, vp, vp]
+        for name in ("ss_welford_update", "ss_welford_sigma", "ss_density"):
+            getattr(L, name).restype = i32
         for name in ("ss_signum_pack", "ss_majority_vote", "ss_sign_apply", "ss_signum_vote_step",
                      "ss_stream_copy", "ss_signum_pack_warmup", "ss_vote_sum", "ss_sum_apply",
                      "ss_signum_vote_step_ex"):
@@ -231,3 +236,30 @@ def stream_copy(dst, src, nbytes, stream=None):
     """ss_stream_copy: measurement aid, dst <- src"""
     L = load_library()
     _check("ss_stream_copy", L.ss_stream_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)))
+
+
+def welford_update(g, mean, m2, n, d=None, stream=None):
+    """ss_welford_update: fold the n-th gradient (n counts from 1) into mean / m2"""
+    L = load_library()
+    d = mean.numel() if d is None else d
+    gp = _dev(g, (torch.float32, torch.bfloat16), d, "g")
+    _check("ss_welford_update", L.ss_welford_update(gp, _grad_dtype(g), _dev(mean, torch.float32, d, "mean"),
+                                                    _dev(m2, torch.float32, d, "m2"), n, d, _stream(stream)))
+
+
+def welford_sigma(m2, n, sigma, d=None, stream=None):
+    """ss_welford_sigma: sigma <- sqrt(m2 / n)"""
+    L = load_library()
+    d = m2.numel() if d is None else d
+    _check("ss_welford_sigma", L.ss_welford_sigma(_dev(m2, torch.float32, d, "m2"), n,
+                                                  _dev(sigma, torch.float32, d, "sigma"), d, _stream(stream)))
+    return sigma
+
+
+def density(v, out, d=None, stream=None):
+    """ss_density: out (3 float64 on the device) <- |v|_1, |v|_2^2, phi(v)"""
+    L = load_library()
+    d = v.numel() if d is None else d
+    vp = _dev(v, torch.float32, d, "v") if d else None
+    _check("ss_density", L.ss_density(vp, d, _dev(out, torch.float64, 3, "out"), _stream(stream)))
+    return out

@@ -6,6 +6,7 @@
 
 #include "step_kernels.hpp"
 #include "vote_apply_kernels.hpp"
+#include "stats_kernels.hpp"
 
 namespace {
 
@@ -334,6 +335,74 @@ int ss_sum_apply(float *x, const int8_t *sums, float delta, size_t d, void *hip_
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
     ss::sum_apply_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
+    return launch_status();
+}
+
+int ss_welford_update(const void *g, ss_dtype gdt, float *mean, float *m2, uint64_t n, size_t d, void *hip_stream) {
+    if (gdt != SS_F32 && gdt != SS_BF16) return SS_ERR_DTYPE;
+    if (n < 1 || n > (1ull << 24)) return SS_ERR_ARG;   // n must be exact in fp32
+    if (d == 0) return SS_OK;
+    if (!g || !mean || !m2) return SS_ERR_NULL;
+    if (!aligned16(g) || !aligned16(mean) || !aligned16(m2)) return SS_ERR_ALIGN;
+    constexpr int R = 2;
+    const Tiling t = make_tiling(d, R, false);
+    ss::WelfordArgs a;
+    a.g = g;
+    a.mean = mean;
+    a.m2 = m2;
+    a.n = (float)n;
+    a.d = d;
+    a.n_tiles = t.n_tiles;
+    const size_t grid = t.n_tiles + t.tail_blocks;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (gdt == SS_F32)
+        ss::welford_update_kernel<R, ss::F32Grad><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    else
+        ss::welford_update_kernel<R, ss::Bf16Grad><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    return launch_status();
+}
+
+int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d, void *hip_stream) {
+    if (n < 1 || n > (1ull << 24)) return SS_ERR_ARG;
+    if (d == 0) return SS_OK;
+    if (!m2 || !sigma) return SS_ERR_NULL;
+    if (!aligned16(m2) || !aligned16(sigma)) return SS_ERR_ALIGN;
+    constexpr int R = 4;
+    const Tiling t = make_tiling(d, R, false);
+    ss::SigmaArgs a;
+    a.m2 = m2;
+    a.sigma = sigma;
+    a.n = (float)n;
+    a.d = d;
+    a.n_tiles = t.n_tiles;
+    const size_t grid = t.n_tiles + t.tail_blocks;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::welford_sigma_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
+    return launch_status();
+}
+
+int ss_density(const float *v, size_t d, double *out, void *hip_stream) {
+    if (!out) return SS_ERR_NULL;
+    if (d > 0 && !v) return SS_ERR_NULL;
+    if (!aligned16(v) || !aligned16(out)) return SS_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    ss::density_clear_kernel<<<dim3(1), dim3(64), 0, stream>>>(out);
+    int rc = launch_status();
+    if (rc != SS_OK || d == 0) return rc;
+    constexpr int R = 8;
+    // Every block ends with three atomics on one cache line, which the memory
+    // side serialises (measured: 16384 blocks cost 150 us in atomics alone), so
+    // the grid is small and each block loops over tiles.
+    const size_t kMaxBlocks = d < (32u << 20) ? 256 : 512;
+    ss::DensityArgs a;
+    a.v = v;
+    a.out = out;
+    a.d = d;
+    a.n_tiles = d / ((size_t)R * ss::kRowCoords);
+    size_t grid = a.n_tiles < kMaxBlocks ? a.n_tiles : kMaxBlocks;
+    if (grid == 0) grid = 1;
+    ss::density_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
     return launch_status();
 }
 

@@ -125,3 +125,21 @@ def test_variant_entry_points_validate_arguments(lib):
     assert lib.ss_sum_apply(a, odd, 0.1, 8, None) == -3
     assert lib.ss_signum_pack_warmup(a, 5, None, 0.9, a, 8, None) == -4
     assert lib.ss_signum_pack_warmup(None, 0, None, 0.9, a, 8, None) == -1
+
+
+def test_statistics_entry_points_validate_arguments(lib):
+    a = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    u64 = ctypes.c_uint64
+    assert lib.ss_welford_update(a, 0, a, a, u64(0), 8, None) == -5            # n counts from 1
+    assert lib.ss_welford_update(a, 0, a, a, u64((1 << 24) + 1), 8, None) == -5  # n must be exact in fp32
+    assert lib.ss_welford_update(a, 3, a, a, u64(1), 8, None) == -4
+    assert lib.ss_welford_update(None, 0, a, a, u64(1), 8, None) == -1
+    assert lib.ss_welford_update(a, 0, odd, a, u64(1), 8, None) == -3
+    assert lib.ss_welford_update(None, 0, None, None, u64(1), 0, None) == 0
+    assert lib.ss_welford_sigma(a, u64(0), a, 8, None) == -5
+    assert lib.ss_welford_sigma(None, u64(2), a, 8, None) == -1
+    assert lib.ss_welford_sigma(a, u64(2), odd, 8, None) == -3
+    assert lib.ss_density(a, 8, None, None) == -1
+    assert lib.ss_density(None, 8, a, None) == -1
+    assert lib.ss_density(a, 8, odd, None) == -3
