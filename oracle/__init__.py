@@ -43,6 +43,10 @@ def lib():
         L.sso_density.argtypes = [vp, sz, vp]
         L.sso_welford_update.argtypes = [vp, i32, vp, vp, ctypes.c_uint64, sz]
         L.sso_welford_sigma.argtypes = [vp, ctypes.c_uint64, vp, sz]
+        L.sso_signum_pack_ternary.argtypes = [vp, i32, vp, f32, f32, vp, vp, sz]
+        L.sso_quorum_vote.argtypes = [vp, vp, i32, i32, vp, vp, sz]
+        L.sso_ternary_apply.argtypes = [vp, vp, vp, f32, sz]
+        L.sso_signum_vote_step_ternary.argtypes = [vp, i32, vp, i32, f32, f32, i32, f32, vp, vp, vp, sz]
         _lib = L
     return _lib
 
@@ -224,3 +228,41 @@ def welford_sigma(m2, n):
     sigma = np.empty_like(m2)
     _check(lib().sso_welford_sigma(_ptr(m2), int(n), _ptr(sigma), len(m2)), "sso_welford_sigma")
     return sigma
+
+
+def signum_pack_ternary(g, m, beta, tau, d=None):
+    """returns (neg bits, zero bits)"""
+    d = len(g) if d is None else d
+    gdt = _grad_dtype(g)
+    _need(g, g.dtype, d, "g")
+    if m is not None:
+        _need(m, np.float32, d, "m")
+    neg, zero = new_bits(d), new_bits(d)
+    _check(lib().sso_signum_pack_ternary(_ptr(g), gdt, _ptr(m) if m is not None else None,
+                                         float(np.float32(beta)), float(np.float32(tau)), _ptr(neg), _ptr(zero), d),
+           "sso_signum_pack_ternary")
+    return neg, zero
+
+
+def quorum_vote(neg, zero, quorum, d):
+    vneg, vzero = new_bits(d), new_bits(d)
+    _check(lib().sso_quorum_vote(_ptr_array(neg), _ptr_array(zero), len(neg), int(quorum), _ptr(vneg), _ptr(vzero), d),
+           "sso_quorum_vote")
+    return vneg, vzero
+
+
+def ternary_apply(x, neg, zero, delta, d=None):
+    d = len(x) if d is None else d
+    _check(lib().sso_ternary_apply(_ptr(x), _ptr(neg), _ptr(zero), float(np.float32(delta)), d), "sso_ternary_apply")
+
+
+def signum_vote_step_ternary(g, m, beta, tau, quorum, delta, x, d=None):
+    M = len(g)
+    d = len(x) if d is None else d
+    gdt = _grad_dtype(g[0])
+    vneg, vzero = new_bits(d), new_bits(d)
+    _check(lib().sso_signum_vote_step_ternary(_ptr_array(g), gdt, _ptr_array(m) if m is not None else None, M,
+                                              float(np.float32(beta)), float(np.float32(tau)), int(quorum),
+                                              float(np.float32(delta)), _ptr(x), _ptr(vneg), _ptr(vzero), d),
+           "sso_signum_vote_step_ternary")
+    return vneg, vzero

@@ -23,6 +23,13 @@
  *   sso_signum_pack_warmup  Theorem 3's warm-up iteration: momentum is
  *                     accumulated as usual, the sign is taken from the gradient.
  *   sso_signum_vote_step_ex  the whole step with either or both variants.
+ *   sso_*_ternary, sso_quorum_vote  "majority vote with abstention" sketched in
+ *                     Section 6 (Discussion): workers may send 0, the server
+ *                     sends 0 unless a quorum agrees.  PARITY UNPINNED as far
+ *                     as the paper goes: it gives neither the workers'
+ *                     criterion nor the quorum rule.  The reading below is
+ *                     this build's; under it the arithmetic is exact and the
+ *                     routines are pinned by brute force like the others.
  *   sso_density       equation (1): phi(v) = |v|_1^2 / (d |v|_2^2).
  *   sso_welford_update, sso_welford_sigma  the single-pass mean / variance of a
  *                     sequence of stochastic gradients that Section 3 uses to
@@ -51,6 +58,14 @@
  *     each operation rounded once (division and square root correctly
  *     rounded), n converted to fp32 (exact below 2^24);
  *     sigma = sqrt(m2 / n): the population standard deviation over the pass.
+ *   abstention (reading, not the paper's): a worker abstains at a coordinate
+ *     when |v| < tau, v = m (or g without momentum), tau >= 0 given by the
+ *     caller; otherwise it votes sign(v).  The server sums the votes
+ *     S = (#plus) - (#minus) and answers sign(S) if |S| >= Q, else 0, with the
+ *     quorum Q >= 1 given by the caller.  x moves by -delta * answer, not at
+ *     all where the answer is 0.  A ternary vector is two bit planes with the
+ *     usual layout: "negative" bits and "zero" bits (never both set).  With
+ *     tau = 0, Q = 1 and odd M this is exactly Algorithm 3.
  *   C(beta) is evaluated in double precision with beta^C built by repeated
  *     multiplication; the smallest positive integer meeting both conditions
  *     of Theorem 3 is returned, exactly as the theorem states it.
@@ -430,4 +445,104 @@ int sso_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d)
         sigma[i] = __builtin_sqrtf(var);
     }
     return SSO_OK;
+}
+
+/* ---- majority vote with abstention (Section 6, Discussion; reading above) ---- */
+
+/* worker: momentum as in Algorithm 2 (m may be NULL), then a ternary vote */
+int sso_signum_pack_ternary(const void *g, int gdt, float *m, float beta,
+                            float tau, uint32_t *neg, uint32_t *zero, size_t d)
+{
+    if (gdt != SSO_F32 && gdt != SSO_BF16) return SSO_ERR_DTYPE;
+    if (!(tau >= 0.0f)) return SSO_ERR_ARG;
+    if (d == 0) return SSO_OK;
+    if (!g || !neg || !zero) return SSO_ERR_NULL;
+    memset(neg, 0, sso_packed_bytes(d));
+    memset(zero, 0, sso_packed_bytes(d));
+    const float one_minus_beta = 1.0f - beta;
+    for (size_t i = 0; i < d; ++i) {
+        float gi = grad_at(g, gdt, i);
+        float v = gi;
+        if (m) {
+            float t1 = beta * m[i];
+            float t2 = one_minus_beta * gi;
+            m[i] = t1 + t2;
+            v = m[i];
+        }
+        float mag = v < 0.0f ? -v : v;
+        if (mag < tau)
+            set_bit(zero, i); /* abstain */
+        else if (v < 0.0f)
+            set_bit(neg, i);
+    }
+    return SSO_OK;
+}
+
+/* server: answer_i = sign(S_i) if |S_i| >= quorum else 0 */
+int sso_quorum_vote(const uint32_t *const *neg, const uint32_t *const *zero,
+                    int M, int quorum, uint32_t *voted_neg,
+                    uint32_t *voted_zero, size_t d)
+{
+    if (M < 1) return SSO_ERR_BAD_M;
+    if (quorum < 1) return SSO_ERR_ARG;
+    if (d == 0) return SSO_OK;
+    if (!neg || !zero || !voted_neg || !voted_zero) return SSO_ERR_NULL;
+    memset(voted_neg, 0, sso_packed_bytes(d));
+    memset(voted_zero, 0, sso_packed_bytes(d));
+    for (size_t i = 0; i < d; ++i) {
+        int sum = 0;
+        for (int w = 0; w < M; ++w) {
+            if (bit_at(zero[w], i)) continue; /* abstained */
+            sum += bit_at(neg[w], i) ? -1 : +1;
+        }
+        if (sum <= -quorum)
+            set_bit(voted_neg, i);
+        else if (sum < quorum)
+            set_bit(voted_zero, i);
+    }
+    return SSO_OK;
+}
+
+/* worker: x_i <- x_i - delta * answer_i */
+int sso_ternary_apply(float *x, const uint32_t *neg, const uint32_t *zero,
+                      float delta, size_t d)
+{
+    if (d == 0) return SSO_OK;
+    if (!x || !neg || !zero) return SSO_ERR_NULL;
+    for (size_t i = 0; i < d; ++i) {
+        if (bit_at(zero, i)) continue;
+        if (bit_at(neg, i))
+            x[i] = x[i] + delta;
+        else
+            x[i] = x[i] - delta;
+    }
+    return SSO_OK;
+}
+
+/* the three in sequence over M workers */
+int sso_signum_vote_step_ternary(const void *const *g, int gdt, float *const *m,
+                                 int M, float beta, float tau, int quorum,
+                                 float delta, float *x, uint32_t *voted_neg,
+                                 uint32_t *voted_zero, size_t d)
+{
+    if (M < 1) return SSO_ERR_BAD_M;
+    if (d == 0) return SSO_OK;
+    if (!g || !x || !voted_neg || !voted_zero) return SSO_ERR_NULL;
+    size_t words = sso_packed_bytes(d) / 4;
+    uint32_t *store = malloc(2 * (size_t)M * words * 4);
+    const uint32_t **negs = malloc((size_t)M * sizeof *negs);
+    const uint32_t **zeros = malloc((size_t)M * sizeof *zeros);
+    int rc = (store && negs && zeros) ? SSO_OK : SSO_ERR_ARG;
+    for (int w = 0; w < M && rc == SSO_OK; ++w) {
+        uint32_t *n = store + (size_t)(2 * w) * words, *z = n + words;
+        negs[w] = n;
+        zeros[w] = z;
+        rc = sso_signum_pack_ternary(g[w], gdt, m ? m[w] : NULL, beta, tau, n, z, d);
+    }
+    if (rc == SSO_OK) rc = sso_quorum_vote(negs, zeros, M, quorum, voted_neg, voted_zero, d);
+    if (rc == SSO_OK) rc = sso_ternary_apply(x, voted_neg, voted_zero, delta, d);
+    free(store);
+    free(negs);
+    free(zeros);
+    return rc;
 }
