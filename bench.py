@@ -47,9 +47,10 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
-    ap.add_argument("--variant", default="default", choices=["default", "warmup", "sum", "sum_out", "welford", "density"],
+    ap.add_argument("--variant", default="default", choices=["default", "warmup", "sum", "sum_out", "ternary", "welford", "density"],
                     help="default: Algorithms 2+3; warmup: Theorem 3 warm-up iteration; sum: '(good)' "
                          "update; sum_out: '(good)' update that also writes the int8 vote sums; "
+                         "ternary: vote with abstention (tau = 0.05, quorum 2); "
                          "welford / density: the gradient-statistics kernels of Section 3 on one worker's gradient")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target length of the oracle timing")
@@ -79,7 +80,8 @@ def main():
     stream = torch.cuda.current_stream()
 
     flags = {"default": None, "warmup": ss.STEP_WARMUP, "sum": ss.STEP_SUM_UPDATE,
-             "sum_out": ss.STEP_SUM_UPDATE, "welford": -1, "density": -1}[args.variant]
+             "sum_out": ss.STEP_SUM_UPDATE, "ternary": -2, "welford": -1, "density": -1}[args.variant]
+    voted_zero = ss.new_bits(d, dev) if args.variant == "ternary" else None
     sums = torch.empty(d, dtype=torch.int8, device=dev) if args.variant == "sum_out" else None
     if args.variant == "welford":
         w_mean, w_m2 = torch.zeros(d, device=dev), torch.zeros(d, device=dev)
@@ -92,6 +94,8 @@ def main():
             ss.welford_update(g[0], w_mean, w_m2, 7, stream=stream)
         elif args.variant == "density":
             ss.density(g32, phi, stream=stream)
+        elif args.variant == "ternary":
+            ss.signum_vote_step_ternary(g, m, beta, 0.05, 2, cfg.delta, x, voted, voted_zero, stream=stream)
         elif flags is None:
             ss.signum_vote_step(g, m, beta, cfg.delta, x, voted, None, stream=stream)
         else:
@@ -117,7 +121,8 @@ def main():
     kernel_ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
     avg_kernel_ms = sum(kernel_ms) / len(kernel_ms)
 
-    bytes_per_launch = (algorithmic_bytes_per_coordinate(cfg) + (1 if sums is not None else 0)) * d
+    bytes_per_launch = (algorithmic_bytes_per_coordinate(cfg) + (1 if sums is not None else 0)
+                        + (0.125 if args.variant == "ternary" else 0)) * d
     if args.variant == "welford":      # read g, mean, m2; write mean, m2
         bytes_per_launch = ((4 if cfg.grad_dtype == "f32" else 2) + 16) * d
     if args.variant == "density":      # read v
@@ -190,7 +195,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: d=%d %s gradients, M=%d workers, beta=%s, delta=%g, fused ss_signum_vote_step%s"
                                % (cfg.name, d, cfg.grad_dtype, M, cfg.beta, cfg.delta,
-                                  "" if flags is None else "_ex variant=" + args.variant)},
+                                  "" if flags is None else " variant=" + args.variant)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic() if (args.workload == "C3" and flags is None) else None},
         "cpu_baseline": cpu,

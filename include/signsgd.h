@@ -181,6 +181,47 @@ int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m,
                            int8_t *sums_out, size_t d, unsigned flags,
                            void *hip_stream);
 
+/* ---- majority vote with abstention (Section 6, Discussion) ----
+ *
+ * The paper only sketches this extension: workers send their vote unless they
+ * are very unsure about the sign, in which case they send zero; the server
+ * sends zero back when no quorum is reached.  It gives neither the workers'
+ * criterion nor the quorum rule, so the rule below is THIS LIBRARY'S READING
+ * (parity with the paper is unpinned; parity with the CPU oracle is exact):
+ *   worker   abstains at coordinate i when |v_i| < tau, v = m (g without
+ *            momentum), tau >= 0; otherwise votes sign(v_i) as in Algorithm 3
+ *   server   S_i = (#plus) - (#minus); answer sign(S_i) if |S_i| >= quorum,
+ *            otherwise 0 (quorum >= 1)
+ *   update   x_i <- x_i - delta * answer_i (x_i untouched where the answer is 0)
+ * A ternary vector is two packed bit planes with the layout of CONVENTIONS:
+ * `neg` (bit set: -1) and `zero` (bit set: 0); never both set in what the
+ * library writes; where both are set in an input, `zero` wins.  With tau = 0,
+ * quorum = 1 and odd M this is exactly Algorithm 3.
+ */
+
+/* worker: momentum update as in ss_signum_pack (m may be NULL), then the ternary
+ * vote of this worker.  neg, zero: out, ss_packed_bytes(d) bytes each. */
+int ss_signum_pack_ternary(const void *g, ss_dtype gdt, float *m, float beta,
+                           float tau, uint32_t *neg, uint32_t *zero, size_t d,
+                           void *hip_stream);
+
+/* server: neg, zero = host arrays of M device pointers (the workers' planes);
+ * voted_neg, voted_zero: out, ss_packed_bytes(d) bytes each. */
+int ss_quorum_vote(const uint32_t *const *neg, const uint32_t *const *zero,
+                   int M, int quorum, uint32_t *voted_neg, uint32_t *voted_zero,
+                   size_t d, void *hip_stream);
+
+/* worker: x <- x - delta * answer, the answer given by its two planes */
+int ss_ternary_apply(float *x, const uint32_t *neg, const uint32_t *zero,
+                     float delta, size_t d, void *hip_stream);
+
+/* the three in one pass; arguments as for ss_signum_vote_step */
+int ss_signum_vote_step_ternary(const void *const *g, ss_dtype gdt,
+                                float *const *m, int M, float beta, float tau,
+                                int quorum, float delta, float *x,
+                                uint32_t *voted_neg, uint32_t *voted_zero,
+                                size_t d, void *hip_stream);
+
 /* ---- gradient statistics (Section 3: equation (1) and Figure 1) ---- */
 
 /*

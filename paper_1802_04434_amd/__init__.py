@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     packed_words, sign_apply, signum_pack, signum_pack_warmup, signum_vote_step,
     signum_vote_step_ex, stream_copy, sum_apply, vote_sum, warmup_length,
     density, welford_sigma, welford_update,
+    quorum_vote, signum_pack_ternary, signum_vote_step_ternary, ternary_apply,
 )

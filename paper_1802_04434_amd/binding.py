@@ -60,6 +60,13 @@ def load_library():
         L.ss_welford_update.argtypes = [vp, i32, vp, vp, ctypes.c_uint64, sz, vp]
         L.ss_welford_sigma.argtypes = [vp, ctypes.c_uint64, vp, sz, vp]
         L.ss_density.argtypes = [vp, sz, vp, vp]
+        L.ss_signum_pack_ternary.argtypes = [vp, i32, vp, f32, f32, vp, vp, sz, vp]
+        L.ss_quorum_vote.argtypes = [vp, vp, i32, i32, vp, vp, sz, vp]
+        L.ss_ternary_apply.argtypes = [vp, vp, vp, f32, sz, vp]
+        L.ss_signum_vote_step_ternary.argtypes = [vp, i32, vp, i32, f32, f32, i32, f32, vp, vp, vp, sz, vp]
+        for name in ("ss_signum_pack_ternary", "ss_quorum_vote", "ss_ternary_apply",
+                     "ss_signum_vote_step_ternary"):
+            getattr(L, name).restype = i32
         for name in ("ss_welford_update", "ss_welford_sigma", "ss_density"):
             getattr(L, name).restype = i32
         for name in ("ss_signum_pack", "ss_majority_vote", "ss_sign_apply", "ss_signum_vote_step",
@@ -263,3 +270,52 @@ def density(v, out, d=None, stream=None):
     vp = _dev(v, torch.float32, d, "v") if d else None
     _check("ss_density", L.ss_density(vp, d, _dev(out, torch.float64, 3, "out"), _stream(stream)))
     return out
+
+
+def signum_pack_ternary(g, m, beta, tau, neg, zero, d=None, stream=None):
+    """ss_signum_pack_ternary: momentum update, then this worker's ternary vote"""
+    L = load_library()
+    d = g.numel() if d is None else d
+    n = L.ss_packed_bytes(d) // 4
+    _check("ss_signum_pack_ternary", L.ss_signum_pack_ternary(
+        _dev(g, (torch.float32, torch.bfloat16), d, "g"), _grad_dtype(g),
+        _dev(m, torch.float32, d, "m") if m is not None else None, beta, tau,
+        _dev(neg, _BITS, n, "neg"), _dev(zero, _BITS, n, "zero"), d, _stream(stream)))
+
+
+def quorum_vote(neg, zero, quorum, voted_neg, voted_zero, d, stream=None):
+    """ss_quorum_vote: the server's ternary answer from the workers' planes"""
+    L = load_library()
+    n = L.ss_packed_bytes(d) // 4
+    np_ = [_dev(t, _BITS, n, "neg[%d]" % i) for i, t in enumerate(neg)]
+    zp = [_dev(t, _BITS, n, "zero[%d]" % i) for i, t in enumerate(zero)]
+    if len(np_) != len(zp):
+        raise ValueError("one neg and one zero plane per worker")
+    _check("ss_quorum_vote", L.ss_quorum_vote(_ptr_array(np_), _ptr_array(zp), len(np_), quorum,
+                                              _dev(voted_neg, _BITS, n, "voted_neg"),
+                                              _dev(voted_zero, _BITS, n, "voted_zero"), d, _stream(stream)))
+
+
+def ternary_apply(x, neg, zero, delta, d=None, stream=None):
+    """ss_ternary_apply: x <- x - delta * answer"""
+    L = load_library()
+    d = x.numel() if d is None else d
+    n = L.ss_packed_words(d)
+    _check("ss_ternary_apply", L.ss_ternary_apply(_dev(x, torch.float32, d, "x"), _dev(neg, _BITS, n, "neg"),
+                                                  _dev(zero, _BITS, n, "zero"), delta, d, _stream(stream)))
+
+
+def signum_vote_step_ternary(g, m, beta, tau, quorum, delta, x, voted_neg, voted_zero, d=None, stream=None):
+    """ss_signum_vote_step_ternary: the whole step with abstention in one pass"""
+    L = load_library()
+    M = len(g)
+    d = x.numel() if d is None else d
+    n = L.ss_packed_bytes(d) // 4
+    gp = [_dev(t, g[0].dtype, d, "g[%d]" % i) for i, t in enumerate(g)]
+    mp = [_dev(t, torch.float32, d, "m[%d]" % i) for i, t in enumerate(m)] if m is not None else None
+    if mp is not None and len(mp) != M:
+        raise ValueError("one momentum buffer per worker")
+    _check("ss_signum_vote_step_ternary", L.ss_signum_vote_step_ternary(
+        _ptr_array(gp), _grad_dtype(g[0]), _ptr_array(mp) if mp is not None else None, M, beta, tau, quorum, delta,
+        _dev(x, torch.float32, d, "x"), _dev(voted_neg, _BITS, n, "voted_neg"),
+        _dev(voted_zero, _BITS, n, "voted_zero"), d, _stream(stream)))

@@ -7,6 +7,7 @@
 #include "step_kernels.hpp"
 #include "vote_apply_kernels.hpp"
 #include "stats_kernels.hpp"
+#include "ternary_kernels.hpp"
 
 namespace {
 
@@ -168,6 +169,35 @@ int launch_vote_any(const uint32_t *const *packed, int M, uint32_t *voted, size_
     ss::vote_kernel_any<<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
     return launch_status();
 }
+
+// launch helpers of the ternary (vote with abstention) kernels
+template <bool HAS_M, bool VOTE, typename G>
+int launch_ternary(ss::TernaryStepArgs &a, size_t d, hipStream_t stream) {
+    constexpr int R = 2;
+    const Tiling t = make_tiling(d, R, true);
+    a.n_tiles = t.n_tiles;
+    a.words_total = t.words_total;
+    const size_t grid = t.n_tiles + t.tail_blocks;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    // several workers over a large vector: same cap on resident blocks as the binary step
+    if (VOTE && a.M >= 2 && d >= kStreamingMinD)
+        ss::ternary_step_kernel<R, kStreamLdsHold, HAS_M, VOTE, G>
+            <<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    else
+        ss::ternary_step_kernel<R, 0, HAS_M, VOTE, G><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    return launch_status();
+}
+
+template <bool VOTE>
+int dispatch_ternary(ss::TernaryStepArgs &a, ss_dtype gdt, bool has_m, size_t d, hipStream_t stream) {
+    if (has_m) {
+        if (gdt == SS_F32) return launch_ternary<true, VOTE, ss::F32Grad>(a, d, stream);
+        return launch_ternary<true, VOTE, ss::Bf16Grad>(a, d, stream);
+    }
+    if (gdt == SS_F32) return launch_ternary<false, VOTE, ss::F32Grad>(a, d, stream);
+    return launch_ternary<false, VOTE, ss::Bf16Grad>(a, d, stream);
+}
+
 
 }  // namespace
 
@@ -404,6 +434,112 @@ int ss_density(const float *v, size_t d, double *out, void *hip_stream) {
     if (grid == 0) grid = 1;
     ss::density_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
     return launch_status();
+}
+
+// ---- majority vote with abstention ----
+
+int ss_signum_pack_ternary(const void *g, ss_dtype gdt, float *m, float beta, float tau, uint32_t *neg,
+                           uint32_t *zero, size_t d, void *hip_stream) {
+    if (gdt != SS_F32 && gdt != SS_BF16) return SS_ERR_DTYPE;
+    if (!(tau >= 0.0f)) return SS_ERR_ARG;
+    if (d == 0) return SS_OK;
+    if (!g || !neg || !zero) return SS_ERR_NULL;
+    if (!aligned16(g) || !aligned16(m) || !aligned16(neg) || !aligned16(zero)) return SS_ERR_ALIGN;
+    ss::TernaryStepArgs a{};
+    a.g[0] = g;
+    a.m[0] = m;
+    a.neg_out = neg;
+    a.zero_out = zero;
+    a.beta = beta;
+    a.omb = 1.0f - beta;
+    a.tau = tau;
+    a.M = 1;
+    a.quorum = 1;
+    a.d = d;
+    return dispatch_ternary<false>(a, gdt, m != nullptr, d, static_cast<hipStream_t>(hip_stream));
+}
+
+int ss_quorum_vote(const uint32_t *const *neg, const uint32_t *const *zero, int M, int quorum,
+                   uint32_t *voted_neg, uint32_t *voted_zero, size_t d, void *hip_stream) {
+    if (M < 1 || M > SS_MAX_WORKERS) return SS_ERR_BAD_M;
+    if (quorum < 1) return SS_ERR_ARG;
+    if (d == 0) return SS_OK;
+    if (!neg || !zero || !voted_neg || !voted_zero) return SS_ERR_NULL;
+    for (int w = 0; w < M; ++w)
+        if (!neg[w] || !zero[w]) return SS_ERR_NULL;
+    if (!aligned16(voted_neg) || !aligned16(voted_zero)) return SS_ERR_ALIGN;
+    for (int w = 0; w < M; ++w)
+        if (!aligned16(neg[w]) || !aligned16(zero[w])) return SS_ERR_ALIGN;
+    ss::QuorumVoteArgs a{};
+    for (int w = 0; w < M; ++w) {
+        a.neg[w] = neg[w];
+        a.zero[w] = zero[w];
+    }
+    a.voted_neg = voted_neg;
+    a.voted_zero = voted_zero;
+    a.M = M;
+    a.quorum = quorum;
+    a.d = d;
+    a.words_total = ss_packed_bytes(d) / 4;
+    const size_t grid = (a.words_total + ss::kBlock - 1) / ss::kBlock;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::quorum_vote_kernel<<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
+    return launch_status();
+}
+
+int ss_ternary_apply(float *x, const uint32_t *neg, const uint32_t *zero, float delta, size_t d,
+                     void *hip_stream) {
+    if (d == 0) return SS_OK;
+    if (!x || !neg || !zero) return SS_ERR_NULL;
+    if (!aligned16(x) || !aligned16(neg) || !aligned16(zero)) return SS_ERR_ALIGN;
+    constexpr int R = 4;
+    const Tiling t = make_tiling(d, R, false);
+    ss::TernaryApplyArgs a;
+    a.x = x;
+    a.neg = neg;
+    a.zero = zero;
+    a.delta = delta;
+    a.d = d;
+    a.n_tiles = t.n_tiles;
+    const size_t grid = t.n_tiles + t.tail_blocks;
+    if (grid > kMaxGrid) return SS_ERR_ARG;
+    ss::ternary_apply_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
+    return launch_status();
+}
+
+int ss_signum_vote_step_ternary(const void *const *g, ss_dtype gdt, float *const *m, int M, float beta, float tau,
+                                int quorum, float delta, float *x, uint32_t *voted_neg, uint32_t *voted_zero,
+                                size_t d, void *hip_stream) {
+    if (M < 1 || M > SS_MAX_WORKERS) return SS_ERR_BAD_M;
+    if (gdt != SS_F32 && gdt != SS_BF16) return SS_ERR_DTYPE;
+    if (!(tau >= 0.0f) || quorum < 1) return SS_ERR_ARG;
+    if (d == 0) return SS_OK;
+    if (!g || !x || !voted_neg || !voted_zero) return SS_ERR_NULL;
+    for (int w = 0; w < M; ++w) {
+        if (!g[w]) return SS_ERR_NULL;
+        if (m && !m[w]) return SS_ERR_NULL;
+    }
+    if (!aligned16(x) || !aligned16(voted_neg) || !aligned16(voted_zero)) return SS_ERR_ALIGN;
+    for (int w = 0; w < M; ++w) {
+        if (!aligned16(g[w])) return SS_ERR_ALIGN;
+        if (m && !aligned16(m[w])) return SS_ERR_ALIGN;
+    }
+    ss::TernaryStepArgs a{};
+    for (int w = 0; w < M; ++w) {
+        a.g[w] = g[w];
+        a.m[w] = m ? m[w] : nullptr;
+    }
+    a.x = x;
+    a.voted_neg = voted_neg;
+    a.voted_zero = voted_zero;
+    a.beta = beta;
+    a.omb = 1.0f - beta;
+    a.delta = delta;
+    a.tau = tau;
+    a.M = M;
+    a.quorum = quorum;
+    a.d = d;
+    return dispatch_ternary<true>(a, gdt, m != nullptr, d, static_cast<hipStream_t>(hip_stream));
 }
 
 int ss_stream_copy(void *dst, const void *src, size_t nbytes, void *hip_stream) {

@@ -143,3 +143,27 @@ def test_statistics_entry_points_validate_arguments(lib):
     assert lib.ss_density(a, 8, None, None) == -1
     assert lib.ss_density(None, 8, a, None) == -1
     assert lib.ss_density(a, 8, odd, None) == -3
+
+
+def test_abstention_entry_points_validate_arguments(lib):
+    a = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    one = (ctypes.c_void_p * 1)(0x1000)
+    f = ctypes.c_float
+    assert lib.ss_signum_pack_ternary(a, 0, None, f(0.9), f(-0.1), a, a, 8, None) == -5      # tau < 0
+    assert lib.ss_signum_pack_ternary(a, 0, None, f(0.9), f(float("nan")), a, a, 8, None) == -5
+    assert lib.ss_signum_pack_ternary(a, 0, None, f(0.9), f(0.1), None, a, 8, None) == -1
+    assert lib.ss_signum_pack_ternary(a, 0, None, f(0.9), f(0.1), a, odd, 8, None) == -3
+    assert lib.ss_signum_pack_ternary(None, 0, None, f(0.9), f(0.1), None, None, 0, None) == 0
+    assert lib.ss_quorum_vote(one, one, 1, 0, a, a, 8, None) == -5                           # quorum >= 1
+    assert lib.ss_quorum_vote(one, one, 65, 1, a, a, 8, None) == -2
+    assert lib.ss_quorum_vote(one, None, 1, 1, a, a, 8, None) == -1
+    assert lib.ss_quorum_vote(one, one, 1, 1, a, odd, 8, None) == -3
+    assert lib.ss_ternary_apply(a, None, a, f(0.1), 8, None) == -1
+    assert lib.ss_ternary_apply(odd, a, a, f(0.1), 8, None) == -3
+    step = lib.ss_signum_vote_step_ternary
+    assert step(one, 0, None, 1, f(0.9), f(0.1), 0, f(0.1), a, a, a, 8, None) == -5
+    assert step(one, 0, None, 0, f(0.9), f(0.1), 1, f(0.1), a, a, a, 8, None) == -2
+    assert step(one, 0, None, 1, f(0.9), f(0.1), 1, f(0.1), a, None, a, 8, None) == -1
+    assert step(one, 0, None, 1, f(0.9), f(0.1), 1, f(0.1), a, a, odd, 8, None) == -3
+    assert step(one, 9, None, 1, f(0.9), f(0.1), 1, f(0.1), a, a, a, 8, None) == -4
