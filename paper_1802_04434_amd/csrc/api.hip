@@ -46,20 +46,21 @@ inline Tiling make_tiling(size_t d, int rows, bool covers_padding) {
 // ------------------------------------------------------------------------
 // Launch shapes of the step kernel (see step_kernels.hpp for the reasoning).
 //   streaming shape, d >= kStreamingMinD: one worker at a time (BW = 1),
-//     kStreamRows rows per block, kStreamLdsHold bytes of LDS held per block
-//     so that two blocks share a compute unit (~32 KB of loads in flight)
+//     kStreamRows rows per block, and kStreamLdsHold bytes of dynamic LDS
+//     requested per block - which no kernel touches - so that only two blocks
+//     fit in a compute unit's 160 KB (~32 KB of loads in flight per unit)
 //   latency shape, smaller d: all workers' loads at once, no cap
 #ifndef SS_STREAM_ROWS
 #define SS_STREAM_ROWS 2
 #endif
 #ifndef SS_STREAM_LDS_HOLD
-#define SS_STREAM_LDS_HOLD (80 * 1024)
+#define SS_STREAM_LDS_HOLD (64 * 1024)
 #endif
 #ifndef SS_STREAM_MIN_D
 #define SS_STREAM_MIN_D (1u << 20)
 #endif
 constexpr int kStreamRows = SS_STREAM_ROWS;
-constexpr int kStreamLdsHold = SS_STREAM_LDS_HOLD;
+constexpr unsigned kStreamLdsHold = SS_STREAM_LDS_HOLD;
 constexpr size_t kStreamingMinD = SS_STREAM_MIN_D;
 
 constexpr int latency_rows(int m, bool has_m) {
@@ -89,15 +90,15 @@ void fill_step_args(ss::StepArgs<NPTR> &a, int M, const void *const *g, float *c
     a.d = d;
 }
 
-template <int MT, int NPTR, int BW, int R, int LDS_HOLD, bool HAS_M, bool VOTE, typename G>
-int launch_step_shape(ss::StepArgs<NPTR> &a, size_t d, hipStream_t stream) {
+template <int MT, int NPTR, int BW, int R, bool HAS_M, bool VOTE, typename G>
+int launch_step_shape(ss::StepArgs<NPTR> &a, size_t d, unsigned lds_hold, hipStream_t stream) {
     const Tiling t = make_tiling(d, R, true);
     a.n_tiles = t.n_tiles;
     a.words_total = t.words_total;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::step_kernel<MT, NPTR, BW, R, LDS_HOLD, HAS_M, VOTE, G>
-        <<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    ss::step_kernel<MT, NPTR, BW, R, HAS_M, VOTE, G>
+        <<<dim3((unsigned)grid), dim3(ss::kBlock), lds_hold, stream>>>(a);
     return launch_status();
 }
 
@@ -120,13 +121,13 @@ int launch_step_m(int M, const void *const *g, float *const *m, uint32_t *const 
     if constexpr (MT == 1) {
         // a single worker is two or three streams whatever the shape: no cap needed
         constexpr int R = VOTE ? 2 : 4;
-        return launch_step_shape<1, NPTR, 1, R, 0, HAS_M, VOTE, G>(a, d, stream);
+        return launch_step_shape<1, NPTR, 1, R, HAS_M, VOTE, G>(a, d, 0, stream);
     } else {
         if (d >= kStreamingMinD)
-            return launch_step_shape<MT, NPTR, 1, kStreamRows, kStreamLdsHold, HAS_M, VOTE, G>(a, d, stream);
+            return launch_step_shape<MT, NPTR, 1, kStreamRows, HAS_M, VOTE, G>(a, d, kStreamLdsHold, stream);
         constexpr int R = MT > 0 ? latency_rows(MT, HAS_M) : 1;
         constexpr int BW = MT > 0 ? latency_batch(MT) : 8;
-        return launch_step_shape<MT, NPTR, BW, R, 0, HAS_M, VOTE, G>(a, d, stream);
+        return launch_step_shape<MT, NPTR, BW, R, HAS_M, VOTE, G>(a, d, 0, stream);
     }
 }
 
@@ -180,11 +181,8 @@ int launch_ternary(ss::TernaryStepArgs &a, size_t d, hipStream_t stream) {
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
     // several workers over a large vector: same cap on resident blocks as the binary step
-    if (VOTE && a.M >= 2 && d >= kStreamingMinD)
-        ss::ternary_step_kernel<R, kStreamLdsHold, HAS_M, VOTE, G>
-            <<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
-    else
-        ss::ternary_step_kernel<R, 0, HAS_M, VOTE, G><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
+    const unsigned lds_hold = (VOTE && a.M >= 2 && d >= kStreamingMinD) ? kStreamLdsHold : 0;
+    ss::ternary_step_kernel<R, HAS_M, VOTE, G><<<dim3((unsigned)grid), dim3(ss::kBlock), lds_hold, stream>>>(a);
     return launch_status();
 }
 

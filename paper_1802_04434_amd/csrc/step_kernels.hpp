@@ -20,9 +20,9 @@
 //    more DRAM rows into them, and the rate drops by 5-10 % - the more streams
 //    (workers) the worse.  For large d the kernel therefore walks the workers
 //    ONE AT A TIME (BW = 1, a block touches two input streams and one output
-//    stream at any moment) and caps the resident blocks per compute unit by
-//    having every block hold a slice of LDS it does not otherwise need
-//    (LDS_HOLD bytes; two 256-thread blocks per unit at 80 KB each).
+//    stream at any moment) and the launch caps the resident blocks per compute
+//    unit by asking for dynamic LDS that the kernel never touches (64 KB per
+//    block: two 256-thread blocks fit in a unit's 160 KB).
 //    Small d is latency bound instead: there all M workers' loads go out
 //    together (BW = M) and nothing is held back.
 #pragma once
@@ -78,33 +78,17 @@ __device__ __forceinline__ int sum_at(uint32_t counts, int k, int M) {
     return M - 2 * (int)((counts >> (8 * k)) & 0xFFu);
 }
 
-// Occupancy governor: a block that declares BYTES of LDS keeps other blocks
-// off its compute unit (160 KB of LDS per unit on gfx950).  The memory is
-// never used for data; the impossible branch only keeps the allocation alive.
-template <int BYTES>
-__device__ __forceinline__ void hold_lds(bool never, uint32_t *sink) {
-    if constexpr (BYTES > 0) {
-        __shared__ uint32_t held[BYTES / 4];
-        if (never) {
-            held[threadIdx.x] = threadIdx.x;
-            *sink = held[(threadIdx.x * 7) % (BYTES / 4)];
-        }
-    }
-}
-
 // MT  > 0: number of workers known at compile time (M == MT)
 // MT == 0: a.M workers, looped at run time in batches of BW
 // BW     : workers whose loads are issued together
 // R      : rows (of kRowCoords coordinates) per block
-// LDS_HOLD: bytes of LDS held per block to cap the blocks per compute unit
-template <int MT, int NPTR, int BW, int R, int LDS_HOLD, bool HAS_M, bool VOTE, typename G>
+template <int MT, int NPTR, int BW, int R, bool HAS_M, bool VOTE, typename G>
 __global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int M = MT > 0 ? MT : a.M;
     const int T = M / 2 + 1;
     const size_t tile = blockIdx.x;
-    hold_lds<LDS_HOLD>(a.words_total == 0, a.p.packed[0]);   // words_total >= 4 whenever a kernel runs
 
     if (tile < a.n_tiles) {
         size_t q[R];

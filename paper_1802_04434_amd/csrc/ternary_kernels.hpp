@@ -12,7 +12,7 @@
 //
 // The kernels mirror the binary ones: a streaming kernel for the worker's pack
 // and for the fused step (one worker at a time, same lane geometry, optional
-// LDS hold), a small server kernel and an apply kernel.
+// cap on resident blocks at launch), a small server kernel and an apply kernel.
 #pragma once
 #include "step_kernels.hpp"
 #include "vote_apply_kernels.hpp"
@@ -45,13 +45,12 @@ __device__ __forceinline__ float step_ternary(float x, float delta, uint32_t ans
     return (answer & 2u) ? x : ((answer & 1u) ? x + delta : x - delta);
 }
 
-template <int R, int LDS_HOLD, bool HAS_M, bool VOTE, typename G>
+template <int R, bool HAS_M, bool VOTE, typename G>
 __global__ __launch_bounds__(kBlock) void ternary_step_kernel(const TernaryStepArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int M = a.M;
     const size_t tile = blockIdx.x;
-    hold_lds<LDS_HOLD>(a.words_total == 0, a.voted_neg);
 
     if (tile < a.n_tiles) {
         size_t q[R];
