@@ -168,3 +168,101 @@ def test_c4_even_m_ties_full_size(ss, oracle):
 def test_c5_bf16_large_full_size(ss, oracle):
     assert synth.C5.d % 32 == 17 and synth.C5.d % 4 == 1
     run_config(ss, oracle, synth.C5, sampled_chunks(synth.C5, extra=2))
+
+
+def test_c3_variants_full_size(ss, oracle):
+    """The variants of the step at the headline size: warm-up + "(good)" update with
+    the int8 sums, vote with abstention, and Welford + density; sampled chunks
+    against the oracle, every coordinate against properties evaluated with torch."""
+    cfg = synth.C3.scaled(d=synth.C3.d, steps=3)
+    d, M = cfg.d, cfg.M
+    chunks = sampled_chunks(cfg, extra=1)
+    g = [torch.empty(d, device=DEV) for _ in range(M)]
+    mus = [synth.mu_chunk(cfg, c, DEV) for c in range(cfg.n_chunks)]
+    x0 = torch.cat([synth.x0_chunk(cfg, c, DEV) for c in range(cfg.n_chunks)])
+    delta_t = torch.tensor(cfg.delta, dtype=torch.float32, device=DEV)
+
+    # ---- warm-up + sum update
+    m = [torch.zeros(d, device=DEV) for _ in range(M)]
+    x = x0.clone()
+    voted = ss.new_bits(d, DEV)
+    sums = torch.empty(d, dtype=torch.int8, device=DEV)
+    host = {c: {"m": [np.zeros(cfg.chunk_range(c)[1] - cfg.chunk_range(c)[0], np.float32) for _ in range(M)],
+                "x": x[cfg.chunk_range(c)[0]:cfg.chunk_range(c)[1]].cpu().numpy().copy()} for c in chunks}
+    flags = ss.STEP_WARMUP | ss.STEP_SUM_UPDATE
+    for k in range(cfg.steps):
+        fill_gradients(cfg, k, g, mus, None)
+        x_before = x.clone()
+        voted.fill_(-1)
+        sums.fill_(99)
+        ss.signum_vote_step_ex(g, m, cfg.beta, cfg.delta, x, voted, None, sums, flags)
+        torch.cuda.synchronize()
+        count = torch.zeros(d, dtype=torch.int32, device=DEV)
+        for w in range(M):
+            count += g[w] < 0                                  # warm-up: the vote is on sign(g)
+        assert torch.equal(sums.to(torch.int32), M - 2 * count)
+        assert torch.equal(unpack_device(voted[: (d + 31) // 32], d), 2 * count > M)
+        want_x = x_before - delta_t * sums.float()
+        assert torch.equal(x.view(torch.int32), want_x.view(torch.int32))
+        for c in chunks:
+            lo, hi = cfg.chunk_range(c)
+            st = host[c]
+            wv, _, ws = oracle.signum_vote_step_ex([synth.as_numpy(g[w][lo:hi]) for w in range(M)], st["m"],
+                                                   cfg.beta, cfg.delta, st["x"], flags)
+            assert np.array_equal(voted[lo // 32: lo // 32 + len(wv)].cpu().numpy().view(np.uint32), wv)
+            assert np.array_equal(sums[lo:hi].cpu().numpy(), ws)
+            assert np.array_equal(x[lo:hi].cpu().numpy().view(np.uint32), st["x"].view(np.uint32))
+            for w in range(M):
+                assert np.array_equal(m[w][lo:hi].cpu().numpy().view(np.uint32), st["m"][w].view(np.uint32))
+
+    # ---- vote with abstention (tau = 0.05, quorum 3), continuing from that state
+    tau, Q = 0.05, 3
+    vneg, vzero = ss.new_bits(d, DEV), ss.new_bits(d, DEV)
+    for k in range(2):
+        fill_gradients(cfg, 10 + k, g, mus, None)
+        x_before = x.clone()
+        ss.signum_vote_step_ternary(g, m, cfg.beta, tau, Q, cfg.delta, x, vneg, vzero)
+        torch.cuda.synchronize()
+        S = torch.zeros(d, dtype=torch.int32, device=DEV)
+        tau_t = torch.tensor(tau, dtype=torch.float32, device=DEV)
+        for w in range(M):
+            votes = torch.where(m[w].abs() < tau_t, 0, torch.where(m[w] < 0, -1, 1))
+            S += votes.to(torch.int32)
+        neg_bits = unpack_device(vneg[: (d + 31) // 32], d)
+        zero_bits = unpack_device(vzero[: (d + 31) // 32], d)
+        assert torch.equal(neg_bits, S <= -Q) and torch.equal(zero_bits, S.abs() < Q)
+        want_x = torch.where(zero_bits, x_before, torch.where(neg_bits, x_before + delta_t, x_before - delta_t))
+        assert torch.equal(x.view(torch.int32), want_x.view(torch.int32))
+        for c in chunks:
+            lo, hi = cfg.chunk_range(c)
+            st = host[c]
+            wn, wz = oracle.signum_vote_step_ternary([synth.as_numpy(g[w][lo:hi]) for w in range(M)], st["m"],
+                                                     cfg.beta, tau, Q, cfg.delta, st["x"])
+            assert np.array_equal(vneg[lo // 32: lo // 32 + len(wn)].cpu().numpy().view(np.uint32), wn)
+            assert np.array_equal(vzero[lo // 32: lo // 32 + len(wz)].cpu().numpy().view(np.uint32), wz)
+            assert np.array_equal(x[lo:hi].cpu().numpy().view(np.uint32), st["x"].view(np.uint32))
+
+    # ---- Welford over the workers' gradients of one step, then the two densities
+    mean, m2 = torch.zeros(d, device=DEV), torch.zeros(d, device=DEV)
+    hw = {c: (np.zeros(cfg.chunk_range(c)[1] - cfg.chunk_range(c)[0], np.float32),
+              np.zeros(cfg.chunk_range(c)[1] - cfg.chunk_range(c)[0], np.float32)) for c in chunks}
+    for w in range(M):
+        ss.welford_update(g[w], mean, m2, w + 1)
+        for c in chunks:
+            lo, hi = cfg.chunk_range(c)
+            oracle.welford_update(synth.as_numpy(g[w][lo:hi]), hw[c][0], hw[c][1], w + 1)
+    sigma = torch.empty(d, device=DEV)
+    ss.welford_sigma(m2, M, sigma)
+    for c in chunks:
+        lo, hi = cfg.chunk_range(c)
+        assert np.array_equal(mean[lo:hi].cpu().numpy().view(np.uint32), hw[c][0].view(np.uint32))
+        assert np.array_equal(m2[lo:hi].cpu().numpy().view(np.uint32), hw[c][1].view(np.uint32))
+        assert np.array_equal(sigma[lo:hi].cpu().numpy().view(np.uint32),
+                              oracle.welford_sigma(hw[c][1], M).view(np.uint32))
+    out = torch.empty(3, dtype=torch.float64, device=DEV)
+    for vec in (mean, sigma):
+        ss.density(vec, out)
+        want = oracle.density(vec.cpu().numpy())
+        got = out.cpu().numpy()
+        assert got[0] == pytest.approx(want[0], rel=1e-12) and got[1] == pytest.approx(want[1], rel=1e-12)
+        assert got[2] == pytest.approx(want[2], rel=3e-12)
