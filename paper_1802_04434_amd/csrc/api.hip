@@ -29,7 +29,7 @@ inline int launch_status() {
 // how the coordinate range is cut for a kernel that handles R rows per block
 struct Tiling {
     size_t n_tiles;      // blocks on the vector path
-    size_t tail_blocks;  // blocks of 256 scalar coordinates, zero padding included
+    size_t tail_blocks;  // blocks of kBlock scalar coordinates, zero padding included
     size_t words_total;
 };
 
@@ -102,13 +102,13 @@ int launch_step_shape(ss::StepArgs<NPTR> &a, size_t d, unsigned lds_hold, hipStr
     return launch_status();
 }
 
-// MT > 0: M fixed at compile time; MT == 0: any M up to SS_MAX_WORKERS
 // what distinguishes the variants of the step (see ss_step_flags)
 struct StepVariant {
     unsigned flags;
     int8_t *sums;
 };
 
+// MT > 0: M fixed at compile time; MT == 0: any M up to SS_MAX_WORKERS
 template <int MT, bool HAS_M, bool VOTE, typename G>
 int launch_step_m(int M, const void *const *g, float *const *m, uint32_t *const *packed, float beta, float delta,
                   float *x, uint32_t *voted, StepVariant var, size_t d, hipStream_t stream) {
@@ -195,7 +195,6 @@ int dispatch_ternary(ss::TernaryStepArgs &a, ss_dtype gdt, bool has_m, size_t d,
     if (gdt == SS_F32) return launch_ternary<false, VOTE, ss::F32Grad>(a, d, stream);
     return launch_ternary<false, VOTE, ss::Bf16Grad>(a, d, stream);
 }
-
 
 }  // namespace
 
