@@ -266,3 +266,55 @@ def test_c3_variants_full_size(ss, oracle):
         got = out.cpu().numpy()
         assert got[0] == pytest.approx(want[0], rel=1e-12) and got[1] == pytest.approx(want[1], rel=1e-12)
         assert got[2] == pytest.approx(want[2], rel=3e-12)
+
+
+def test_more_than_2_to_32_coordinates(ss, oracle):
+    """Maximum-size case: d just above 2^32, so that any 32-bit index in a kernel
+    or in the launch arithmetic would wrap.  One worker, bf16 gradient, no
+    momentum (26 GB of state).  Every coordinate is checked with torch, the
+    first and last stretches against the oracle."""
+    d = (1 << 32) + 4096 + 5
+    n = 1 << 20                                    # stretch compared with the oracle at both ends
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(42)
+    g = torch.empty(d, device=DEV, dtype=torch.bfloat16)
+    x = torch.empty(d, device=DEV)
+    step = 1 << 28
+    for lo in range(0, d, step):
+        hi = min(d, lo + step)
+        g[lo:hi] = torch.randn(hi - lo, device=DEV, generator=gen).to(torch.bfloat16)
+        x[lo:hi] = torch.randn(hi - lo, device=DEV, generator=gen) * 0.05
+    ends = [(0, n), (d - n - 5, d)]                 # the second one starts on a word boundary
+    assert all(lo % 32 == 0 for lo, _ in ends)
+    host_x = [x[lo:hi].cpu().numpy().copy() for lo, hi in ends]
+    voted = ss.new_bits(d, DEV)
+    voted.fill_(-1)
+    delta = 1e-3
+    delta_t = torch.tensor(delta, dtype=torch.float32, device=DEV)
+    x_before = x.clone()
+    ss.signum_vote_step([g], None, 0.0, delta, x, voted)
+    torch.cuda.synchronize()
+    for lo in range(0, d, step):
+        hi = min(d, lo + step)
+        bits = unpack_device(voted[lo // 32:(hi + 31) // 32], hi - lo)
+        assert torch.equal(bits, g[lo:hi].float() < 0), lo
+        want = torch.where(bits, x_before[lo:hi] + delta_t, x_before[lo:hi] - delta_t)
+        assert torch.equal(x[lo:hi].view(torch.int32), want.view(torch.int32)), lo
+    tail_words = voted[d // 32:].cpu().numpy().view(np.uint32)
+    assert sum(int(v) << (32 * i) for i, v in enumerate(tail_words)) >> (d % 32) == 0
+    for (lo, hi), hx in zip(ends, host_x):
+        want_voted = oracle.signum_vote_step([synth.as_numpy(g[lo:hi])], None, 0.0, delta, hx, threads=16)
+        got = voted[lo // 32: lo // 32 + len(want_voted)].cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, want_voted)
+        assert np.array_equal(x[lo:hi].cpu().numpy().view(np.uint32), hx.view(np.uint32))
+    # the stand-alone kernels at the same size: pack, vote (one voter), apply
+    packed = ss.new_bits(d, DEV)
+    ss.signum_pack(g, None, 0.0, packed)
+    assert torch.equal(packed, voted)
+    voted2 = ss.new_bits(d, DEV)
+    ss.majority_vote([packed], voted2, d)
+    assert torch.equal(voted2, voted)
+    ss.sign_apply(x_before, voted2, delta)
+    assert torch.equal(x_before.view(torch.int32), x.view(torch.int32))
+    del g, x, x_before, voted, voted2, packed
+    torch.cuda.empty_cache()
