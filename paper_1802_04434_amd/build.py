@@ -34,5 +34,25 @@ def build(extra_flags=(), out=LIB, verbose=False):
     return out
 
 
+ABI_CHECK = os.path.join(HERE, "abi_check")
+
+
+def build_abi_check(verbose=False):
+    """The stand-alone C++ host program that drives the library without Python
+    (csrc/abi_check.cpp); it finds libsignsgd.so next to itself."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    tmp = ABI_CHECK + ".tmp%d" % os.getpid()
+    # plain host C++: only the HIP runtime API (hipMalloc, hipMemcpy, streams) and the library
+    cmd = ["g++", "-O2", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(rocm, "include"),
+           os.path.join(CSRC, "abi_check.cpp"), "-o", tmp, "-L" + HERE, "-lsignsgd",
+           "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, ABI_CHECK)
+    return ABI_CHECK
+
+
 if __name__ == "__main__":
     print(build(extra_flags=sys.argv[1:], verbose=True))
+    print(build_abi_check(verbose=True))
