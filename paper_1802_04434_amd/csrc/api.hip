@@ -63,6 +63,11 @@ constexpr int kStreamRows = SS_STREAM_ROWS;
 constexpr unsigned kStreamLdsHold = SS_STREAM_LDS_HOLD;
 constexpr size_t kStreamingMinD = SS_STREAM_MIN_D;
 
+// when ss_signum_vote_step is given packed_out buffers it may run as M + 2 launches (see there)
+constexpr size_t kSplitMinD = (size_t)1 << 24;
+constexpr int kSplitMinWorkersF32 = 10;
+constexpr int kSplitMinWorkersBf16 = 4;
+
 constexpr int latency_rows(int m, bool has_m) {
     const int streams = m * (has_m ? 2 : 1);
     return streams >= 8 ? 1 : streams >= 4 ? 2 : 4;
@@ -307,6 +312,21 @@ int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m, 
         if (!aligned16(g[w])) return SS_ERR_ALIGN;
         if (m && !aligned16(m[w])) return SS_ERR_ALIGN;
         if (packed_out && !aligned16(packed_out[w])) return SS_ERR_ALIGN;
+    }
+    // Many workers over a large vector, and the caller wants every worker's bits anyway: then
+    // those buffers can carry the signs from launch to launch, and M pack launches + vote + apply
+    // (each touching three streams chip-wide at a time) measured 4-15 % faster than the one-pass
+    // kernel with its 2M+1 input and M+1 output streams.  Same results, bit for bit.
+    if (packed_out && !sums_out && !(flags & SS_STEP_SUM_UPDATE) && d >= kSplitMinD &&
+        M >= (gdt == SS_BF16 ? kSplitMinWorkersBf16 : kSplitMinWorkersF32)) {
+        for (int w = 0; w < M; ++w) {
+            const int rc = signum_pack_impl(g[w], gdt, m ? m[w] : nullptr, beta, packed_out[w], d,
+                                            flags & SS_STEP_WARMUP, hip_stream);
+            if (rc != SS_OK) return rc;
+        }
+        const int rc = ss_majority_vote(packed_out, M, voted, d, hip_stream);
+        if (rc != SS_OK) return rc;
+        return ss_sign_apply(x, voted, delta, d, hip_stream);
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const StepVariant var{flags, sums_out};

@@ -327,3 +327,33 @@ def test_fused_step_large_d_streaming_shape(ss, oracle, M, dtype, momentum):
             for w in range(M):
                 assert_same_floats(m_dev[w], m[w], "m[%d] step %d" % (w, k))
         assert_same_floats(x_dev, x, "x step %d" % k)
+
+
+@pytest.mark.parametrize("M,dtype,flags", [(10, "f32", 0), (12, "f32", 1), (4, "bf16", 0), (5, "bf16", 1)])
+def test_fused_step_with_packed_out_at_many_workers(ss, oracle, M, dtype, flags):
+    # d >= 2^24 with per-worker bits requested: the call may hand the signs
+    # from launch to launch through packed_out; results must not change
+    d = (1 << 24) + 1000 + 21
+    rng = np.random.default_rng(M)
+    g = [make_grad(rng, d, dtype, scale=0.5) for _ in range(M)]
+    m = [make_momentum(rng, d) for _ in range(M)]
+    x = (rng.standard_normal(d) * 0.05).astype(np.float32)
+    g_dev = [t.to(DEV) for t in g]
+    m_dev = [torch.from_numpy(a).to(DEV) for a in m]
+    x_dev = torch.from_numpy(x).to(DEV)
+    voted = dirty_bits(ss, d)
+    packed = [dirty_bits(ss, d) for _ in range(M)]
+    ss.signum_vote_step_ex(g_dev, m_dev, 0.9, 1e-4, x_dev, voted, packed, None, flags)
+    # the same call without packed_out (always the one-pass kernel)
+    m2 = [torch.from_numpy(a).to(DEV) for a in m]
+    x2 = torch.from_numpy(x).to(DEV)
+    voted2 = dirty_bits(ss, d)
+    ss.signum_vote_step_ex(g_dev, m2, 0.9, 1e-4, x2, voted2, None, None, flags)
+    assert torch.equal(voted, voted2) and torch.equal(x_dev.view(torch.int32), x2.view(torch.int32))
+    assert all(torch.equal(a.view(torch.int32), b.view(torch.int32)) for a, b in zip(m_dev, m2))
+    want_voted, want_packed, _ = oracle.signum_vote_step_ex([synth.as_numpy(t) for t in g], m, 0.9, 1e-4, x, flags)
+    assert np.array_equal(bits_np(voted), want_voted)
+    for w in range(M):
+        assert np.array_equal(bits_np(packed[w]), want_packed[w]), w
+        assert_same_floats(m_dev[w], m[w], "m[%d]" % w)
+    assert_same_floats(x_dev, x, "x")
