@@ -81,7 +81,7 @@ __device__ __forceinline__ int sum_at(uint32_t counts, int k, int M) {
 // MT  > 0: number of workers known at compile time (M == MT)
 // MT == 0: a.M workers, looped at run time in batches of BW
 // BW     : workers whose loads are issued together
-// R      : rows (of kRowCoords coordinates) per block
+// R      : rows (of kRowCoords = kBlock * 4 coordinates) per block
 template <int MT, int NPTR, int BW, int R, bool HAS_M, bool VOTE, typename G>
 __global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
     const int tid = threadIdx.x;
