@@ -351,7 +351,13 @@ def test_fused_step_with_packed_out_at_many_workers(ss, oracle, M, dtype, flags)
     ss.signum_vote_step_ex(g_dev, m2, 0.9, 1e-4, x2, voted2, None, None, flags)
     assert torch.equal(voted, voted2) and torch.equal(x_dev.view(torch.int32), x2.view(torch.int32))
     assert all(torch.equal(a.view(torch.int32), b.view(torch.int32)) for a, b in zip(m_dev, m2))
-    want_voted, want_packed, _ = oracle.signum_vote_step_ex([synth.as_numpy(t) for t in g], m, 0.9, 1e-4, x, flags)
+    gh = [synth.as_numpy(t) for t in g]
+    if flags == 0:
+        want_voted, want_packed = oracle.signum_vote_step(gh, m, 0.9, 1e-4, x, want_packed=True, threads=16)
+    else:       # warm-up, from its parts (the threaded oracle entry point has no flags)
+        want_packed = [oracle.signum_pack_warmup(gh[w], m[w], 0.9) for w in range(M)]
+        want_voted = oracle.majority_vote(want_packed, d)
+        oracle.sign_apply(x, want_voted, 1e-4)
     assert np.array_equal(bits_np(voted), want_voted)
     for w in range(M):
         assert np.array_equal(bits_np(packed[w]), want_packed[w]), w
