@@ -31,11 +31,14 @@
  *              with sign(m_w).
  *
  * MEMORY      Every data pointer (g, m, x, packed, voted) is DEVICE memory,
- *             owned by the caller, 16-byte aligned, and no two buffers of one
- *             call may overlap.  Arrays OF pointers (g[], m[], packed[]) are
- *             HOST arrays of M device pointers; they are copied into the
- *             kernel arguments during the call and may be freed on return.
- *             The library allocates nothing and keeps no state between calls.
+ *             owned by the caller and 16-byte aligned.  A buffer that a call
+ *             writes (m, x, packed, voted, sums, ...) may not share a byte with
+ *             any other buffer of that call: SS_ERR_ARG, nothing launched.
+ *             Buffers that are only read may coincide.  Arrays OF pointers
+ *             (g[], m[], packed[]) are HOST arrays of M device pointers; they
+ *             are copied into the kernel arguments during the call and may be
+ *             freed on return.  The library allocates nothing and keeps no
+ *             state between calls.
  * STREAMS     hip_stream is a hipStream_t passed as void* (NULL: the default
  *             stream).  Work is enqueued and the call returns without
  *             synchronising.  Calls are thread safe.
@@ -60,8 +63,9 @@ typedef enum {
     SS_ERR_BAD_M = -2, /* M < 1 or M > SS_MAX_WORKERS */
     SS_ERR_ALIGN = -3, /* a data pointer is not 16-byte aligned */
     SS_ERR_DTYPE = -4, /* unknown gradient dtype */
-    SS_ERR_ARG = -5,   /* any other invalid argument (e.g. d too large) */
-    SS_ERR_HIP = -6    /* the HIP runtime refused the launch; see ss_last_hip_error */
+    SS_ERR_ARG = -5,   /* any other invalid argument (d too large, overlapping buffers, ...) */
+    SS_ERR_HIP = -6,   /* the HIP runtime refused a launch; see ss_last_hip_error */
+    SS_ERR_RANGE = -7  /* the arguments are valid but the answer lies beyond a documented limit */
 } ss_status;
 
 /* gradient element type; momentum and parameters are always fp32 */
@@ -120,7 +124,9 @@ int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d,
  * Normally one kernel launch.  When packed_out is given, d >= 2^24 and there
  * are many workers (10, or 4 with bf16 gradients), the call enqueues M + 2
  * launches that hand the signs over through packed_out, which is faster there;
- * the results are the same.
+ * the results are the same.  Should the runtime refuse one of those launches
+ * (SS_ERR_HIP), the launches before it stay enqueued: some momentum buffers
+ * have then been advanced by this step and x has not.
  */
 int ss_signum_vote_step(const void *const *g, ss_dtype gdt, float *const *m,
                         int M, float beta, float delta, float *x,
@@ -142,8 +148,12 @@ typedef enum {
  * Theorem 3's warm-up length: the smallest positive integer C with
  * (C/2) beta^C <= 1/((1 - beta^2)(C + 1)) and beta^(C+1) <= 1/2, evaluated in
  * double precision (beta^C by repeated multiplication).  Host only, launches
- * nothing.  54 for beta = 0.9.  SS_ERR_ARG unless 0 < beta < 1.
+ * nothing.  54 for beta = 0.9.  SS_ERR_ARG unless 0 < beta < 1.  The search is
+ * linear in C and stops at SS_WARMUP_MAX (about 20 ms of host time): a beta so
+ * close to 1 that C would be larger (beta above roughly 1 - 2e-6) gives
+ * SS_ERR_RANGE.
  */
+#define SS_WARMUP_MAX 10000000L
 long ss_warmup_length(float beta);
 
 /*
@@ -249,14 +259,21 @@ int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d,
 /*
  * Equation (1): the density phi(v) = |v|_1^2 / (d |v|_2^2) of a vector
  * (1 for a fully dense vector, 1/d for a one-hot one).
- *   v    in   d x fp32
- *   out  out  3 doubles in DEVICE memory, 16-byte aligned:
- *             out[0] = |v|_1, out[1] = |v|_2^2, out[2] = phi(v) (0 for the zero vector)
- * The sums are accumulated in fp64 (every term is exact); the order of the
- * last additions is not fixed, so results may differ between runs in the last
- * bits (relative error below 1e-12).  Two launches on hip_stream.
+ *   v          in   d x fp32
+ *   out        out  3 doubles in DEVICE memory, 16-byte aligned:
+ *                   out[0] = |v|_1, out[1] = |v|_2^2, out[2] = phi(v) (0 for the zero vector)
+ *   workspace  i/o  ss_density_workspace_bytes() bytes of DEVICE memory, 16-byte
+ *                   aligned, owned by the caller.  It must be all zero bytes before
+ *                   the first call that uses it; every call that runs to completion
+ *                   leaves it ready for the next one (no clearing in between).  Two
+ *                   calls that may run at the same time need two workspaces.
+ * Both sums are accumulated in fp64 (every term is exact) in an order that
+ * depends on d alone: the same input gives the same bits on every run.  One
+ * kernel launch; the blocks leave partial sums in the workspace and the block
+ * that finishes last adds them up.
  */
-int ss_density(const float *v, size_t d, double *out, void *hip_stream);
+size_t ss_density_workspace_bytes(void);
+int ss_density(const float *v, size_t d, double *out, void *workspace, void *hip_stream);
 
 /* the hipError_t (as int) behind this thread's most recent SS_ERR_HIP; 0 if none */
 int ss_last_hip_error(void);

@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libsignsgd.so")
 _lib = None
 
 _STATUS = {0: "SS_OK", -1: "SS_ERR_NULL", -2: "SS_ERR_BAD_M", -3: "SS_ERR_ALIGN",
-           -4: "SS_ERR_DTYPE", -5: "SS_ERR_ARG", -6: "SS_ERR_HIP"}
+           -4: "SS_ERR_DTYPE", -5: "SS_ERR_ARG", -6: "SS_ERR_HIP", -7: "SS_ERR_RANGE"}
 
 
 class SignSGDError(RuntimeError):
@@ -59,7 +59,9 @@ def load_library():
         L.ss_signum_vote_step_ex.argtypes = [vp, i32, vp, i32, f32, f32, vp, vp, vp, vp, sz, ctypes.c_uint, vp]
         L.ss_welford_update.argtypes = [vp, i32, vp, vp, ctypes.c_uint64, sz, vp]
         L.ss_welford_sigma.argtypes = [vp, ctypes.c_uint64, vp, sz, vp]
-        L.ss_density.argtypes = [vp, sz, vp, vp]
+        L.ss_density.argtypes = [vp, sz, vp, vp, vp]
+        L.ss_density_workspace_bytes.restype = sz
+        L.ss_density_workspace_bytes.argtypes = []
         L.ss_signum_pack_ternary.argtypes = [vp, i32, vp, f32, f32, vp, vp, sz, vp]
         L.ss_quorum_vote.argtypes = [vp, vp, i32, i32, vp, vp, sz, vp]
         L.ss_ternary_apply.argtypes = [vp, vp, vp, f32, sz, vp]
@@ -263,12 +265,18 @@ def welford_sigma(m2, n, sigma, d=None, stream=None):
     return sigma
 
 
-def density(v, out, d=None, stream=None):
+def new_density_workspace(device="cuda"):
+    """zero-filled workspace for ss_density (ss_density_workspace_bytes() bytes)"""
+    return torch.zeros(load_library().ss_density_workspace_bytes() // 8, dtype=torch.int64, device=device)
+
+
+def density(v, out, workspace, d=None, stream=None):
     """ss_density: out (3 float64 on the device) <- |v|_1, |v|_2^2, phi(v)"""
     L = load_library()
     d = v.numel() if d is None else d
     vp = _dev(v, torch.float32, d, "v") if d else None
-    _check("ss_density", L.ss_density(vp, d, _dev(out, torch.float64, 3, "out"), _stream(stream)))
+    wp = _dev(workspace, torch.int64, L.ss_density_workspace_bytes() // 8, "workspace")
+    _check("ss_density", L.ss_density(vp, d, _dev(out, torch.float64, 3, "out"), wp, _stream(stream)))
     return out
 
 

@@ -4,6 +4,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <type_traits>
+
 #include "step_kernels.hpp"
 #include "vote_apply_kernels.hpp"
 #include "stats_kernels.hpp"
@@ -17,8 +20,43 @@ constexpr size_t kMaxGrid = 0x7FFFFFFFull;
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-inline int launch_status() {
-    const hipError_t e = hipGetLastError();
+inline size_t grad_bytes(ss_dtype gdt) { return gdt == SS_BF16 ? 2 : 4; }
+
+// A buffer of one call, for the check that nothing that is written shares a byte
+// with anything else (buffers that are only read may coincide, e.g. one gradient
+// handed in for two workers).
+struct Span {
+    uintptr_t lo, hi;   // [lo, hi); empty spans (NULL pointer or no bytes) never overlap
+    bool written;
+};
+
+inline Span span(const void *p, size_t bytes, bool written) {
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
+    return Span{lo, p ? lo + bytes : lo, written};
+}
+
+// sorts s; true iff a written span overlaps any other span
+inline bool written_spans_overlap(Span *s, int n) {
+    std::sort(s, s + n, [](const Span &a, const Span &b) { return a.lo < b.lo; });
+    uintptr_t end_any = 0, end_written = 0;   // furthest end among the spans seen so far
+    for (int i = 0; i < n; ++i) {
+        if (s[i].lo == s[i].hi) continue;
+        if (s[i].lo < (s[i].written ? end_any : end_written)) return true;
+        end_any = std::max(end_any, s[i].hi);
+        if (s[i].written) end_written = std::max(end_written, s[i].hi);
+    }
+    return false;
+}
+
+// Every kernel takes one argument struct by value.  The status is the launch
+// call's own return value: an error left on this thread by an earlier, unrelated
+// runtime call is neither reported as ours nor cleared.
+template <typename Args>
+int launch(void (*kernel)(Args), size_t grid, unsigned lds_bytes, hipStream_t stream, const Args &a,
+           int block = ss::kBlock) {
+    void *params[1] = {const_cast<Args *>(&a)};
+    const hipError_t e = hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3((unsigned)grid),
+                                         dim3((unsigned)block), params, lds_bytes, stream);
     if (e != hipSuccess) {
         g_last_hip_error = (int)e;
         return SS_ERR_HIP;
@@ -33,35 +71,25 @@ struct Tiling {
     size_t words_total;
 };
 
-inline Tiling make_tiling(size_t d, int rows, bool covers_padding) {
+inline Tiling make_tiling(size_t d, int rows, bool covers_padding, int block = ss::kBlock) {
     Tiling t;
+    const size_t tile = (size_t)rows * block * ss::kQuad;
     t.words_total = ss_packed_bytes(d) / 4;
-    t.n_tiles = d / ((size_t)rows * ss::kRowCoords);
-    const size_t done = t.n_tiles * (size_t)rows * ss::kRowCoords;
+    t.n_tiles = d / tile;
+    const size_t done = t.n_tiles * tile;
     const size_t end = covers_padding ? t.words_total * 32 : d;
-    t.tail_blocks = (end - done + ss::kBlock - 1) / ss::kBlock;
+    t.tail_blocks = (end - done + block - 1) / block;
     return t;
 }
 
 // ------------------------------------------------------------------------
 // Launch shapes of the step kernel (see step_kernels.hpp for the reasoning).
-//   streaming shape, d >= kStreamingMinD: one worker at a time (BW = 1),
-//     kStreamRows rows per block, and kStreamLdsHold bytes of dynamic LDS
-//     requested per block - which no kernel touches - so that only two blocks
-//     fit in a compute unit's 160 KB (~32 KB of loads in flight per unit)
+//   streaming shape, d >= kStreamingMinD and several workers: one worker at a
+//     time, and a reservation of LDS that no kernel touches, sized so that the
+//     wanted number of blocks fits in a compute unit's LDS
 //   latency shape, smaller d: all workers' loads at once, no cap
-#ifndef SS_STREAM_ROWS
-#define SS_STREAM_ROWS 2
-#endif
-#ifndef SS_STREAM_LDS_HOLD
-#define SS_STREAM_LDS_HOLD (64 * 1024)
-#endif
-#ifndef SS_STREAM_MIN_D
-#define SS_STREAM_MIN_D (1u << 20)
-#endif
-constexpr int kStreamRows = SS_STREAM_ROWS;
-constexpr unsigned kStreamLdsHold = SS_STREAM_LDS_HOLD;
-constexpr size_t kStreamingMinD = SS_STREAM_MIN_D;
+constexpr size_t kStreamingMinD = (size_t)1 << 20;
+constexpr int kLdsPerUnitKB = 160;   // what the reservations below assume; checked against the device
 
 // when ss_signum_vote_step is given packed_out buffers it may run as M + 2 launches (see there)
 constexpr size_t kSplitMinD = (size_t)1 << 24;
@@ -95,16 +123,23 @@ void fill_step_args(ss::StepArgs<NPTR> &a, int M, const void *const *g, float *c
     a.d = d;
 }
 
-template <int MT, int NPTR, int BW, int R, bool HAS_M, bool VOTE, typename G>
-int launch_step_shape(ss::StepArgs<NPTR> &a, size_t d, unsigned lds_hold, hipStream_t stream) {
-    const Tiling t = make_tiling(d, R, true);
+template <int MT, int NPTR, int BLOCK, int BW, int R, int HOLD_KB, bool LOADS_FIRST, bool HAS_M, bool VOTE, typename G>
+int launch_step_shape(ss::StepArgs<NPTR> &a, size_t d, hipStream_t stream) {
+    const Tiling t = make_tiling(d, R, true, BLOCK);
     a.n_tiles = t.n_tiles;
     a.words_total = t.words_total;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::step_kernel<MT, NPTR, BW, R, HAS_M, VOTE, G>
-        <<<dim3((unsigned)grid), dim3(ss::kBlock), lds_hold, stream>>>(a);
-    return launch_status();
+    return launch(ss::step_kernel<MT, NPTR, BLOCK, BW, R, HOLD_KB, LOADS_FIRST, HAS_M, VOTE, G>, grid, 0, stream, a, BLOCK);
+}
+
+// LDS of one compute unit of the current device, in KB; 0 if the runtime will not say.  A pure
+// query: nothing is remembered between calls.
+inline int lds_per_unit_kb() {
+    int dev = 0, bytes = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess) return 0;
+    return bytes / 1024;
 }
 
 // what distinguishes the variants of the step (see ss_step_flags)
@@ -123,16 +158,34 @@ int launch_step_m(int M, const void *const *g, float *const *m, uint32_t *const 
     a.warmup = (var.flags & SS_STEP_WARMUP) ? 1 : 0;
     a.sum_update = (var.flags & SS_STEP_SUM_UPDATE) ? 1 : 0;
     a.sums = var.sums;
+    constexpr bool kBf16 = std::is_same<G, ss::Bf16Grad>::value;
     if constexpr (MT == 1) {
         // a single worker is two or three streams whatever the shape: no cap needed
         constexpr int R = VOTE ? 2 : 4;
-        return launch_step_shape<1, NPTR, 1, R, HAS_M, VOTE, G>(a, d, 0, stream);
+        return launch_step_shape<1, NPTR, 256, 1, R, 0, false, HAS_M, VOTE, G>(a, d, stream);
     } else {
-        if (d >= kStreamingMinD)
-            return launch_step_shape<MT, NPTR, 1, kStreamRows, HAS_M, VOTE, G>(a, d, kStreamLdsHold, stream);
+        // Streaming shapes.  Each keeps roughly 16-24 KB of loads in flight per compute unit (see
+        // step_kernels.hpp) and was picked by measurement among block sizes 64-1024, 1-8 workers per
+        // stage, 1-8 rows and 1-5 blocks per unit, with the workloads' own buffer placement.  The
+        // reservations only mean what they should on a part with the LDS size they were sized for.
+        if (d >= kStreamingMinD && lds_per_unit_kb() == kLdsPerUnitKB) {
+            if constexpr (!HAS_M) {
+                // gradients only: four (bf16: eight) loads per lane make up for the missing momentum stream
+                return launch_step_shape<MT, NPTR, 256, 2, kBf16 ? 4 : 2, 64, true, false, VOTE, G>(a, d, stream);
+            } else if constexpr (!kBf16) {
+                // fp32: one 512-thread block per unit, one worker and one row at a time
+                return launch_step_shape<MT, NPTR, 512, 1, 1, 96, true, true, VOTE, G>(a, d, stream);
+            } else {
+                // bf16 gradients (a wave's gradient load is half as long): from four workers on, four
+                // 128-thread blocks per unit that take two workers at a time; below that, two
+                // 256-thread blocks with two rows, the loads left to the compiler's own interleaving
+                if (M >= 4) return launch_step_shape<MT, NPTR, 128, 2, 1, 40, true, true, VOTE, G>(a, d, stream);
+                return launch_step_shape<MT, NPTR, 256, 1, 2, 64, false, true, VOTE, G>(a, d, stream);
+            }
+        }
         constexpr int R = MT > 0 ? latency_rows(MT, HAS_M) : 1;
         constexpr int BW = MT > 0 ? latency_batch(MT) : 8;
-        return launch_step_shape<MT, NPTR, BW, R, HAS_M, VOTE, G>(a, d, 0, stream);
+        return launch_step_shape<MT, NPTR, 256, BW, R, 0, false, HAS_M, VOTE, G>(a, d, stream);
     }
 }
 
@@ -159,8 +212,7 @@ int launch_vote_fixed(const uint32_t *const *packed, uint32_t *voted, size_t d, 
     a.n_vec = ss_packed_bytes(d) / 16;
     const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::vote_kernel<M><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
-    return launch_status();
+    return launch(ss::vote_kernel<M>, grid, 0, stream, a);
 }
 
 int launch_vote_any(const uint32_t *const *packed, int M, uint32_t *voted, size_t d, hipStream_t stream) {
@@ -172,23 +224,27 @@ int launch_vote_any(const uint32_t *const *packed, int M, uint32_t *voted, size_
     a.n_vec = ss_packed_bytes(d) / 16;
     const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::vote_kernel_any<<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
-    return launch_status();
+    return launch(ss::vote_kernel_any, grid, 0, stream, a);
 }
 
 // launch helpers of the ternary (vote with abstention) kernels
-template <bool HAS_M, bool VOTE, typename G>
-int launch_ternary(ss::TernaryStepArgs &a, size_t d, hipStream_t stream) {
-    constexpr int R = 2;
-    const Tiling t = make_tiling(d, R, true);
+template <int BLOCK, int R, int HOLD_KB, bool LOADS_FIRST, bool HAS_M, bool VOTE, typename G>
+int launch_ternary_shape(ss::TernaryStepArgs &a, size_t d, hipStream_t stream) {
+    const Tiling t = make_tiling(d, R, true, BLOCK);
     a.n_tiles = t.n_tiles;
     a.words_total = t.words_total;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    // several workers over a large vector: same cap on resident blocks as the binary step
-    const unsigned lds_hold = (VOTE && a.M >= 2 && d >= kStreamingMinD) ? kStreamLdsHold : 0;
-    ss::ternary_step_kernel<R, HAS_M, VOTE, G><<<dim3((unsigned)grid), dim3(ss::kBlock), lds_hold, stream>>>(a);
-    return launch_status();
+    return launch(ss::ternary_step_kernel<BLOCK, R, HOLD_KB, LOADS_FIRST, HAS_M, VOTE, G>, grid, 0, stream, a, BLOCK);
+}
+
+template <bool HAS_M, bool VOTE, typename G>
+int launch_ternary(ss::TernaryStepArgs &a, size_t d, hipStream_t stream) {
+    // several workers over a large vector: two blocks per unit, one worker at a time (the
+    // one-block-per-unit shape of the binary step measured 7 % slower here)
+    if (VOTE && a.M >= 2 && d >= kStreamingMinD && lds_per_unit_kb() == kLdsPerUnitKB)
+        return launch_ternary_shape<256, 2, 64, false, HAS_M, VOTE, G>(a, d, stream);
+    return launch_ternary_shape<256, 2, 0, false, HAS_M, VOTE, G>(a, d, stream);
 }
 
 template <bool VOTE>
@@ -217,6 +273,9 @@ static int signum_pack_impl(const void *g, ss_dtype gdt, float *m, float beta, u
     if (d == 0) return SS_OK;
     if (!g || !packed) return SS_ERR_NULL;
     if (!aligned16(g) || !aligned16(m) || !aligned16(packed)) return SS_ERR_ALIGN;
+    Span spans[3] = {span(g, d * grad_bytes(gdt), false), span(m, d * sizeof(float), true),
+                     span(packed, ss_packed_bytes(d), true)};
+    if (written_spans_overlap(spans, 3)) return SS_ERR_ARG;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const void *gs[1] = {g};
     float *ms[1] = {m};
@@ -247,13 +306,13 @@ long ss_warmup_length(float beta_f) {
     if (!(beta > 0.0 && beta < 1.0)) return SS_ERR_ARG;
     // smallest C >= 1 with (C/2) beta^C (C+1) (1 - beta^2) <= 1 and beta^(C+1) <= 1/2
     double beta_to_c = 1.0;
-    for (long c = 1; c <= 1000000000L; ++c) {
+    for (long c = 1; c <= SS_WARMUP_MAX; ++c) {
         beta_to_c *= beta;
         const bool bias_settled = 0.5 * (double)c * beta_to_c <= 1.0 / ((1.0 - beta * beta) * ((double)c + 1.0));
         const bool decayed = beta_to_c * beta <= 0.5;
         if (bias_settled && decayed) return c;
     }
-    return SS_ERR_ARG;
+    return SS_ERR_RANGE;
 }
 
 int ss_majority_vote(const uint32_t *const *packed, int M, uint32_t *voted, size_t d, void *hip_stream) {
@@ -265,6 +324,12 @@ int ss_majority_vote(const uint32_t *const *packed, int M, uint32_t *voted, size
     if (!aligned16(voted)) return SS_ERR_ALIGN;
     for (int w = 0; w < M; ++w)
         if (!aligned16(packed[w])) return SS_ERR_ALIGN;
+    {
+        Span spans[SS_MAX_WORKERS + 1];
+        for (int w = 0; w < M; ++w) spans[w] = span(packed[w], ss_packed_bytes(d), false);
+        spans[M] = span(voted, ss_packed_bytes(d), true);
+        if (written_spans_overlap(spans, M + 1)) return SS_ERR_ARG;
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 #define SS_CASE(n) \
     case n: return launch_vote_fixed<n>(packed, voted, d, stream)
@@ -280,6 +345,8 @@ int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d, void *h
     if (d == 0) return SS_OK;
     if (!x || !bits) return SS_ERR_NULL;
     if (!aligned16(x) || !aligned16(bits)) return SS_ERR_ALIGN;
+    Span spans[2] = {span(x, d * sizeof(float), true), span(bits, ss_packed_words(d) * 4, false)};
+    if (written_spans_overlap(spans, 2)) return SS_ERR_ARG;
     constexpr int R = 4;
     const Tiling t = make_tiling(d, R, false);
     ss::ApplyArgs a;
@@ -290,8 +357,7 @@ int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d, void *h
     a.n_tiles = t.n_tiles;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::apply_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
-    return launch_status();
+    return launch(ss::apply_kernel<R>, grid, 0, static_cast<hipStream_t>(hip_stream), a);
 }
 
 int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m, int M, float beta, float delta,
@@ -312,6 +378,19 @@ int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m, 
         if (!aligned16(g[w])) return SS_ERR_ALIGN;
         if (m && !aligned16(m[w])) return SS_ERR_ALIGN;
         if (packed_out && !aligned16(packed_out[w])) return SS_ERR_ALIGN;
+    }
+    {
+        Span spans[3 * SS_MAX_WORKERS + 3];
+        int n = 0;
+        for (int w = 0; w < M; ++w) {
+            spans[n++] = span(g[w], d * grad_bytes(gdt), false);
+            if (m) spans[n++] = span(m[w], d * sizeof(float), true);
+            if (packed_out) spans[n++] = span(packed_out[w], ss_packed_bytes(d), true);
+        }
+        spans[n++] = span(x, d * sizeof(float), true);
+        spans[n++] = span(voted, ss_packed_bytes(d), true);
+        spans[n++] = span(sums_out, d, true);
+        if (written_spans_overlap(spans, n)) return SS_ERR_ARG;
     }
     // Many workers over a large vector, and the caller wants every worker's bits anyway: then
     // those buffers can carry the signs from launch to launch, and M pack launches + vote + apply
@@ -355,22 +434,30 @@ int ss_vote_sum(const uint32_t *const *packed, int M, int8_t *sums, size_t d, vo
     if (!aligned16(sums)) return SS_ERR_ALIGN;
     for (int w = 0; w < M; ++w)
         if (!aligned16(packed[w])) return SS_ERR_ALIGN;
+    {
+        Span spans[SS_MAX_WORKERS + 1];
+        for (int w = 0; w < M; ++w) spans[w] = span(packed[w], ss_packed_bytes(d), false);
+        spans[M] = span(sums, d, true);
+        if (written_spans_overlap(spans, M + 1)) return SS_ERR_ARG;
+    }
     ss::VoteSumArgs a;
     for (int w = 0; w < SS_MAX_WORKERS; ++w) a.packed[w] = w < M ? packed[w] : nullptr;
     a.sums = sums;
     a.M = M;
     a.d = d;
     a.n_halves = (d + 15) / 16;
-    const size_t grid = (a.n_halves + ss::kBlock - 1) / ss::kBlock;
+    const size_t per_block = (size_t)ss::kBlock * ss::kVoteSumRows;
+    const size_t grid = (a.n_halves + per_block - 1) / per_block;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::vote_sum_kernel<<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
-    return launch_status();
+    return launch(ss::vote_sum_kernel, grid, 0, static_cast<hipStream_t>(hip_stream), a);
 }
 
 int ss_sum_apply(float *x, const int8_t *sums, float delta, size_t d, void *hip_stream) {
     if (d == 0) return SS_OK;
     if (!x || !sums) return SS_ERR_NULL;
     if (!aligned16(x) || !aligned16(sums)) return SS_ERR_ALIGN;
+    Span spans[2] = {span(x, d * sizeof(float), true), span(sums, d, false)};
+    if (written_spans_overlap(spans, 2)) return SS_ERR_ARG;
     constexpr int R = 4;
     const Tiling t = make_tiling(d, R, false);
     ss::SumApplyArgs a;
@@ -381,8 +468,7 @@ int ss_sum_apply(float *x, const int8_t *sums, float delta, size_t d, void *hip_
     a.n_tiles = t.n_tiles;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::sum_apply_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
-    return launch_status();
+    return launch(ss::sum_apply_kernel<R>, grid, 0, static_cast<hipStream_t>(hip_stream), a);
 }
 
 int ss_welford_update(const void *g, ss_dtype gdt, float *mean, float *m2, uint64_t n, size_t d, void *hip_stream) {
@@ -391,6 +477,9 @@ int ss_welford_update(const void *g, ss_dtype gdt, float *mean, float *m2, uint6
     if (d == 0) return SS_OK;
     if (!g || !mean || !m2) return SS_ERR_NULL;
     if (!aligned16(g) || !aligned16(mean) || !aligned16(m2)) return SS_ERR_ALIGN;
+    Span spans[3] = {span(g, d * grad_bytes(gdt), false), span(mean, d * sizeof(float), true),
+                     span(m2, d * sizeof(float), true)};
+    if (written_spans_overlap(spans, 3)) return SS_ERR_ARG;
     constexpr int R = 2;
     const Tiling t = make_tiling(d, R, false);
     ss::WelfordArgs a;
@@ -403,11 +492,8 @@ int ss_welford_update(const void *g, ss_dtype gdt, float *mean, float *m2, uint6
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (gdt == SS_F32)
-        ss::welford_update_kernel<R, ss::F32Grad><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
-    else
-        ss::welford_update_kernel<R, ss::Bf16Grad><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
-    return launch_status();
+    if (gdt == SS_F32) return launch(ss::welford_update_kernel<R, ss::F32Grad>, grid, 0, stream, a);
+    return launch(ss::welford_update_kernel<R, ss::Bf16Grad>, grid, 0, stream, a);
 }
 
 int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d, void *hip_stream) {
@@ -415,6 +501,8 @@ int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d, void *
     if (d == 0) return SS_OK;
     if (!m2 || !sigma) return SS_ERR_NULL;
     if (!aligned16(m2) || !aligned16(sigma)) return SS_ERR_ALIGN;
+    Span spans[2] = {span(m2, d * sizeof(float), false), span(sigma, d * sizeof(float), true)};
+    if (written_spans_overlap(spans, 2)) return SS_ERR_ARG;
     constexpr int R = 4;
     const Tiling t = make_tiling(d, R, false);
     ss::SigmaArgs a;
@@ -425,32 +513,34 @@ int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d, void *
     a.n_tiles = t.n_tiles;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::welford_sigma_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
-    return launch_status();
+    return launch(ss::welford_sigma_kernel<R>, grid, 0, static_cast<hipStream_t>(hip_stream), a);
 }
 
-int ss_density(const float *v, size_t d, double *out, void *hip_stream) {
-    if (!out) return SS_ERR_NULL;
-    if (d > 0 && !v) return SS_ERR_NULL;
-    if (!aligned16(v) || !aligned16(out)) return SS_ERR_ALIGN;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    ss::density_clear_kernel<<<dim3(1), dim3(64), 0, stream>>>(out);
-    int rc = launch_status();
-    if (rc != SS_OK || d == 0) return rc;
-    constexpr int R = 8;
-    // Every block ends with three atomics on one cache line, which the memory
-    // side serialises (measured: 16384 blocks cost 150 us in atomics alone), so
-    // the grid is small and each block loops over tiles.
-    const size_t kMaxBlocks = d < (32u << 20) ? 256 : 512;
+size_t ss_density_workspace_bytes(void) { return sizeof(ss::DensityScratch); }
+
+static int density_impl(const float *v, size_t d, double *out, ss::DensityScratch *scratch, hipStream_t stream) {
     ss::DensityArgs a;
     a.v = v;
     a.out = out;
+    a.scratch = scratch;
     a.d = d;
-    a.n_tiles = d / ((size_t)R * ss::kRowCoords);
-    size_t grid = a.n_tiles < kMaxBlocks ? a.n_tiles : kMaxBlocks;
+    a.n_tiles = d / ((size_t)ss::kDensityRows * ss::kRowCoords);
+    // every block gets the same number of tiles (the last one possibly fewer): the grid is a
+    // function of d alone, which is what fixes the order of the additions
+    const size_t per_block = (a.n_tiles + ss::kDensityMaxBlocks - 1) / ss::kDensityMaxBlocks;
+    size_t grid = per_block ? (a.n_tiles + per_block - 1) / per_block : 1;
     if (grid == 0) grid = 1;
-    ss::density_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, stream>>>(a);
-    return launch_status();
+    return launch(ss::density_kernel, grid, 0, stream, a);
+}
+
+int ss_density(const float *v, size_t d, double *out, void *workspace, void *hip_stream) {
+    if (!out || !workspace) return SS_ERR_NULL;
+    if (d > 0 && !v) return SS_ERR_NULL;
+    if (!aligned16(v) || !aligned16(out) || !aligned16(workspace)) return SS_ERR_ALIGN;
+    Span spans[3] = {span(out, 3 * sizeof(double), true), span(workspace, sizeof(ss::DensityScratch), true),
+                     span(v, d * sizeof(float), false)};
+    if (written_spans_overlap(spans, 3)) return SS_ERR_ARG;
+    return density_impl(v, d, out, static_cast<ss::DensityScratch *>(workspace), static_cast<hipStream_t>(hip_stream));
 }
 
 // ---- majority vote with abstention ----
@@ -462,6 +552,9 @@ int ss_signum_pack_ternary(const void *g, ss_dtype gdt, float *m, float beta, fl
     if (d == 0) return SS_OK;
     if (!g || !neg || !zero) return SS_ERR_NULL;
     if (!aligned16(g) || !aligned16(m) || !aligned16(neg) || !aligned16(zero)) return SS_ERR_ALIGN;
+    Span spans[4] = {span(g, d * grad_bytes(gdt), false), span(m, d * sizeof(float), true),
+                     span(neg, ss_packed_bytes(d), true), span(zero, ss_packed_bytes(d), true)};
+    if (written_spans_overlap(spans, 4)) return SS_ERR_ARG;
     ss::TernaryStepArgs a{};
     a.g[0] = g;
     a.m[0] = m;
@@ -487,6 +580,16 @@ int ss_quorum_vote(const uint32_t *const *neg, const uint32_t *const *zero, int 
     if (!aligned16(voted_neg) || !aligned16(voted_zero)) return SS_ERR_ALIGN;
     for (int w = 0; w < M; ++w)
         if (!aligned16(neg[w]) || !aligned16(zero[w])) return SS_ERR_ALIGN;
+    {
+        Span spans[2 * SS_MAX_WORKERS + 2];
+        for (int w = 0; w < M; ++w) {
+            spans[2 * w] = span(neg[w], ss_packed_bytes(d), false);
+            spans[2 * w + 1] = span(zero[w], ss_packed_bytes(d), false);
+        }
+        spans[2 * M] = span(voted_neg, ss_packed_bytes(d), true);
+        spans[2 * M + 1] = span(voted_zero, ss_packed_bytes(d), true);
+        if (written_spans_overlap(spans, 2 * M + 2)) return SS_ERR_ARG;
+    }
     ss::QuorumVoteArgs a{};
     for (int w = 0; w < M; ++w) {
         a.neg[w] = neg[w];
@@ -495,13 +598,12 @@ int ss_quorum_vote(const uint32_t *const *neg, const uint32_t *const *zero, int 
     a.voted_neg = voted_neg;
     a.voted_zero = voted_zero;
     a.M = M;
-    a.quorum = quorum;
+    a.quorum = quorum > M + 1 ? M + 1 : quorum;   // any quorum above M can never be met: same answers
     a.d = d;
-    a.words_total = ss_packed_bytes(d) / 4;
-    const size_t grid = (a.words_total + ss::kBlock - 1) / ss::kBlock;
+    a.n_vec = ss_packed_bytes(d) / 16;
+    const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::quorum_vote_kernel<<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
-    return launch_status();
+    return launch(ss::quorum_vote_kernel, grid, 0, static_cast<hipStream_t>(hip_stream), a);
 }
 
 int ss_ternary_apply(float *x, const uint32_t *neg, const uint32_t *zero, float delta, size_t d,
@@ -509,6 +611,9 @@ int ss_ternary_apply(float *x, const uint32_t *neg, const uint32_t *zero, float 
     if (d == 0) return SS_OK;
     if (!x || !neg || !zero) return SS_ERR_NULL;
     if (!aligned16(x) || !aligned16(neg) || !aligned16(zero)) return SS_ERR_ALIGN;
+    Span spans[3] = {span(x, d * sizeof(float), true), span(neg, ss_packed_words(d) * 4, false),
+                     span(zero, ss_packed_words(d) * 4, false)};
+    if (written_spans_overlap(spans, 3)) return SS_ERR_ARG;
     constexpr int R = 4;
     const Tiling t = make_tiling(d, R, false);
     ss::TernaryApplyArgs a;
@@ -520,8 +625,7 @@ int ss_ternary_apply(float *x, const uint32_t *neg, const uint32_t *zero, float 
     a.n_tiles = t.n_tiles;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::ternary_apply_kernel<R><<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(a);
-    return launch_status();
+    return launch(ss::ternary_apply_kernel<R>, grid, 0, static_cast<hipStream_t>(hip_stream), a);
 }
 
 int ss_signum_vote_step_ternary(const void *const *g, ss_dtype gdt, float *const *m, int M, float beta, float tau,
@@ -540,6 +644,18 @@ int ss_signum_vote_step_ternary(const void *const *g, ss_dtype gdt, float *const
     for (int w = 0; w < M; ++w) {
         if (!aligned16(g[w])) return SS_ERR_ALIGN;
         if (m && !aligned16(m[w])) return SS_ERR_ALIGN;
+    }
+    {
+        Span spans[2 * SS_MAX_WORKERS + 3];
+        int n = 0;
+        for (int w = 0; w < M; ++w) {
+            spans[n++] = span(g[w], d * grad_bytes(gdt), false);
+            if (m) spans[n++] = span(m[w], d * sizeof(float), true);
+        }
+        spans[n++] = span(x, d * sizeof(float), true);
+        spans[n++] = span(voted_neg, ss_packed_bytes(d), true);
+        spans[n++] = span(voted_zero, ss_packed_bytes(d), true);
+        if (written_spans_overlap(spans, n)) return SS_ERR_ARG;
     }
     ss::TernaryStepArgs a{};
     for (int w = 0; w < M; ++w) {
@@ -564,12 +680,13 @@ int ss_stream_copy(void *dst, const void *src, size_t nbytes, void *hip_stream) 
     if (!dst || !src) return SS_ERR_NULL;
     if (!aligned16(dst) || !aligned16(src)) return SS_ERR_ALIGN;
     if (nbytes % 16 != 0) return SS_ERR_ARG;
+    Span spans[2] = {span(dst, nbytes, true), span(src, nbytes, false)};
+    if (written_spans_overlap(spans, 2)) return SS_ERR_ARG;
     const size_t n_vec = nbytes / 16;
     const size_t grid = (n_vec + ss::kBlock * 4 - 1) / (ss::kBlock * 4);
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    ss::copy_kernel<<<dim3((unsigned)grid), dim3(ss::kBlock), 0, static_cast<hipStream_t>(hip_stream)>>>(
-        static_cast<ss::f32x4 *>(dst), static_cast<const ss::f32x4 *>(src), n_vec);
-    return launch_status();
+    const ss::CopyArgs a{static_cast<ss::f32x4 *>(dst), static_cast<const ss::f32x4 *>(src), n_vec};
+    return launch(ss::copy_kernel, grid, 0, static_cast<hipStream_t>(hip_stream), a);
 }
 
 }  // extern "C"

@@ -22,17 +22,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
 
-#ifndef SS_BLOCK_THREADS
-#define SS_BLOCK_THREADS 256
-#endif
-#ifndef SS_NT_LOAD
-#define SS_NT_LOAD 1
-#endif
-#ifndef SS_NT_STORE
-#define SS_NT_STORE 1
-#endif
-
-constexpr int kBlock = SS_BLOCK_THREADS;   // threads per block
+constexpr int kBlock = 256;          // threads per block
 constexpr int kQuad = 4;             // coordinates per lane per row
 constexpr int kRowCoords = kBlock * kQuad;   // 1024
 
@@ -40,19 +30,11 @@ constexpr int kRowCoords = kBlock * kQuad;   // 1024
 // non-temporal and keep them out of the way of anything cached.
 template <typename T>
 __device__ __forceinline__ T ld_stream(const T *p) {
-#if SS_NT_LOAD
     return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
 }
 template <typename T>
 __device__ __forceinline__ void st_stream(T *p, T v) {
-#if SS_NT_STORE
     __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
 }
 
 // bf16 -> fp32 is exact: the bf16 pattern is the upper half of the fp32

@@ -78,17 +78,71 @@ __device__ __forceinline__ int sum_at(uint32_t counts, int k, int M) {
     return M - 2 * (int)((counts >> (8 * k)) & 0xFFu);
 }
 
+// One stage of the vector path: NW consecutive workers starting at w0, R rows.  With
+// LOADS_FIRST every load of the stage is issued before anything waits for one of them;
+// without it the compiler interleaves (for two rows it starts the second row's loads
+// when the first row's momentum has arrived, which keeps fewer bytes in flight).
+template <int NW, int R, int BLOCK, bool LOADS_FIRST, bool HAS_M, typename G, int NPTR>
+__device__ __forceinline__ void step_stage(const StepArgs<NPTR> &a, int w0, const size_t (&q)[R],
+                                           uint32_t (&counts)[R], int lane) {
+    f32x4 gv[R][NW], mv[R][NW];
+#pragma unroll
+    for (int j = 0; j < NW; ++j) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            gv[r][j] = G::load4(a.p.g[w0 + j], q[r]);
+            if (HAS_M) mv[r][j] = ld_stream(reinterpret_cast<const f32x4 *>(a.p.m[w0 + j]) + q[r]);
+        }
+    }
+    if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NW; ++j) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            f32x4 v = gv[r][j];
+            if (HAS_M) {
+                f32x4 m0 = mv[r][j];
+                v.x = momentum(a.beta, a.omb, m0.x, v.x);
+                v.y = momentum(a.beta, a.omb, m0.y, v.y);
+                v.z = momentum(a.beta, a.omb, m0.z, v.z);
+                v.w = momentum(a.beta, a.omb, m0.w, v.w);
+                st_stream(reinterpret_cast<f32x4 *>(a.p.m[w0 + j]) + q[r], v);
+            }
+            // Algorithm 2 votes with sign(m); a warm-up iteration with sign(g)
+            const uint32_t nib = neg_nibble((HAS_M && a.warmup) ? gv[r][j] : v);
+            counts[r] += spread_nibble(nib);
+            if (a.write_packed) {
+                const uint32_t word = combine8(nib, lane);
+                if ((lane & 7) == 0) a.p.packed[w0 + j][q[r] >> 3] = word;
+            }
+        }
+    }
+    if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
+}
+
 // MT  > 0: number of workers known at compile time (M == MT)
-// MT == 0: a.M workers, looped at run time in batches of BW
-// BW     : workers whose loads are issued together
-// R      : rows (of kRowCoords = kBlock * 4 coordinates) per block
-template <int MT, int NPTR, int BW, int R, bool HAS_M, bool VOTE, typename G>
-__global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
+// MT == 0: a.M workers, looped at run time
+// BLOCK  : threads per block (a row is BLOCK * 4 coordinates)
+// BW     : workers per stage (whose loads are issued together); what M leaves
+//          over after the full stages goes one worker at a time
+// R      : rows per block
+// HOLD_KB: kilobytes of LDS the block reserves and never uses, which caps how
+//          many blocks share a compute unit (0: no cap)
+template <int MT, int NPTR, int BLOCK, int BW, int R, int HOLD_KB, bool LOADS_FIRST, bool HAS_M, bool VOTE, typename G>
+__global__ __launch_bounds__(BLOCK) void step_kernel(const StepArgs<NPTR> a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int M = MT > 0 ? MT : a.M;
     const int T = M / 2 + 1;
     const size_t tile = blockIdx.x;
+    if constexpr (HOLD_KB > 0) {
+        // never true (the host rejects such a d); it only keeps the reservation alive
+        __shared__ uint32_t hold[HOLD_KB * 256];
+        if (a.d == ~(size_t)0) {
+            hold[tid] = (uint32_t)a.M;
+            a.p.packed[0][tid] = hold[tid ^ 1];
+        }
+    }
 
     if (tile < a.n_tiles) {
         size_t q[R];
@@ -96,47 +150,15 @@ __global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
         f32x4 xv[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            q[r] = (tile * R + r) * kBlock + tid;
+            q[r] = (tile * R + r) * BLOCK + tid;
             counts[r] = 0;
             if (VOTE) xv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.x) + q[r]);
         }
-        for (int w0 = 0; w0 < M; w0 += BW) {
-            f32x4 gv[R][BW], mv[R][BW];
-#pragma unroll
-            for (int j = 0; j < BW; ++j) {
-                if (w0 + j < M) {
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        gv[r][j] = G::load4(a.p.g[w0 + j], q[r]);
-                        if (HAS_M) mv[r][j] = ld_stream(reinterpret_cast<const f32x4 *>(a.p.m[w0 + j]) + q[r]);
-                    }
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < BW; ++j) {
-                if (w0 + j < M) {
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        f32x4 v = gv[r][j];
-                        if (HAS_M) {
-                            f32x4 m0 = mv[r][j];
-                            v.x = momentum(a.beta, a.omb, m0.x, v.x);
-                            v.y = momentum(a.beta, a.omb, m0.y, v.y);
-                            v.z = momentum(a.beta, a.omb, m0.z, v.z);
-                            v.w = momentum(a.beta, a.omb, m0.w, v.w);
-                            st_stream(reinterpret_cast<f32x4 *>(a.p.m[w0 + j]) + q[r], v);
-                        }
-                        // Algorithm 2 votes with sign(m); a warm-up iteration with sign(g)
-                        const uint32_t nib = neg_nibble((HAS_M && a.warmup) ? gv[r][j] : v);
-                        counts[r] += spread_nibble(nib);
-                        if (a.write_packed) {
-                            const uint32_t word = combine8(nib, lane);
-                            if ((lane & 7) == 0) a.p.packed[w0 + j][q[r] >> 3] = word;
-                        }
-                    }
-                }
-            }
+        int w0 = 0;
+        if constexpr (BW > 1) {
+            for (; w0 + BW <= M; w0 += BW) step_stage<BW, R, BLOCK, LOADS_FIRST, HAS_M, G>(a, w0, q, counts, lane);
         }
+        for (; w0 < M; ++w0) step_stage<1, R, BLOCK, LOADS_FIRST, HAS_M, G>(a, w0, q, counts, lane);
         if (VOTE) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
@@ -165,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void step_kernel(const StepArgs<NPTR> a) {
     // Scalar path for what does not fill a tile: one coordinate per lane, so
     // the 64-bit wave ballot is two packed words in order.  It also writes
     // the zero padding words.
-    const size_t i = a.n_tiles * (size_t)(R * kRowCoords) + (tile - a.n_tiles) * kBlock + tid;
+    const size_t i = a.n_tiles * (size_t)(R * BLOCK * kQuad) + (tile - a.n_tiles) * BLOCK + tid;
     const bool in = i < a.d;
     const size_t word = i >> 5;   // for lanes 0 and 32: the word this half-wave fills
     const bool writes_word = (lane & 31) == 0 && word < a.words_total;

@@ -12,7 +12,7 @@
 //
 // The kernels mirror the binary ones: a streaming kernel for the worker's pack
 // and for the fused step (one worker at a time, same lane geometry, optional
-// cap on resident blocks at launch), a small server kernel and an apply kernel.
+// cap on resident blocks through an LDS reservation), a small server kernel and an apply kernel.
 #pragma once
 #include "step_kernels.hpp"
 #include "vote_apply_kernels.hpp"
@@ -45,12 +45,22 @@ __device__ __forceinline__ float step_ternary(float x, float delta, uint32_t ans
     return (answer & 2u) ? x : ((answer & 1u) ? x + delta : x - delta);
 }
 
-template <int R, bool HAS_M, bool VOTE, typename G>
-__global__ __launch_bounds__(kBlock) void ternary_step_kernel(const TernaryStepArgs a) {
+// BLOCK threads per block, R rows per block, HOLD_KB of LDS reserved to cap the blocks per
+// compute unit, LOADS_FIRST as in the binary step kernel
+template <int BLOCK, int R, int HOLD_KB, bool LOADS_FIRST, bool HAS_M, bool VOTE, typename G>
+__global__ __launch_bounds__(BLOCK) void ternary_step_kernel(const TernaryStepArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int M = a.M;
     const size_t tile = blockIdx.x;
+    if constexpr (HOLD_KB > 0) {
+        // never true (the host rejects such a d); it only keeps the LDS reservation alive
+        __shared__ uint32_t hold[HOLD_KB * 256];
+        if (a.d == ~(size_t)0) {
+            hold[tid] = (uint32_t)a.M;
+            a.voted_neg[tid] = hold[tid ^ 1];
+        }
+    }
 
     if (tile < a.n_tiles) {
         size_t q[R];
@@ -58,7 +68,7 @@ __global__ __launch_bounds__(kBlock) void ternary_step_kernel(const TernaryStepA
         f32x4 xv[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            q[r] = (tile * R + r) * kBlock + tid;
+            q[r] = (tile * R + r) * BLOCK + tid;
             n_neg[r] = 0;
             n_zero[r] = 0;
             if (VOTE) xv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.x) + q[r]);
@@ -70,6 +80,8 @@ __global__ __launch_bounds__(kBlock) void ternary_step_kernel(const TernaryStepA
                 gv[r] = G::load4(a.g[w], q[r]);
                 if (HAS_M) mv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.m[w]) + q[r]);
             }
+            // every load of this worker is in flight before the first result is waited for
+            if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 f32x4 v = gv[r];
@@ -126,7 +138,7 @@ __global__ __launch_bounds__(kBlock) void ternary_step_kernel(const TernaryStepA
     }
 
     // scalar path: what does not fill a tile, and the zero padding words
-    const size_t i = a.n_tiles * (size_t)(R * kRowCoords) + (tile - a.n_tiles) * kBlock + tid;
+    const size_t i = a.n_tiles * (size_t)(R * BLOCK * kQuad) + (tile - a.n_tiles) * BLOCK + tid;
     const bool in = i < a.d;
     const size_t word = i >> 5;
     const bool writes_word = (lane & 31) == 0 && word < a.words_total;
@@ -175,40 +187,83 @@ struct QuorumVoteArgs {
     int M;
     int quorum;
     size_t d;
-    size_t words_total;
+    size_t n_vec;     // 128-bit groups of words, padding included
 };
 
-// one lane per packed word: counts of "-" and of abstentions for its 32
-// coordinates sit in byte lanes of 2 x 8 registers
+// Bit-sliced, like the binary vote: a lane holds 128 coordinates (four words)
+// of every plane.  The numbers of "-" votes (n) and of abstentions (z) are
+// counted into binary planes with a ripple of half adders per worker; then
+// t = 2 n + z is formed plane by plane, and since S = #plus - #minus = M - t,
+//     answer "-"  iff  S <= -Q  iff  t >= M + Q
+//     answer  0   iff  |S| < Q  iff  M - Q < t < M + Q
+// which are two comparisons of t with constants, done from the lowest plane up.
+constexpr int kCountPlanes = 7;    // n, z <= 64
+constexpr int kTotalPlanes = 8;    // t <= 128 + 64
+constexpr int kQuorumBatch = 4;    // workers (two planes each) whose words are loaded together
+
+__device__ __forceinline__ u32x4 splat(uint32_t v) { return u32x4{v, v, v, v}; }
+
+// planes of (t >= c) for a constant c, t given by its binary planes
+__device__ __forceinline__ u32x4 planes_ge(const u32x4 (&t)[kTotalPlanes], int c) {
+    if (c <= 0) return splat(0xFFFFFFFFu);
+    if (c >= (1 << kTotalPlanes)) return splat(0u);
+    u32x4 ge = splat(0xFFFFFFFFu);
+#pragma unroll
+    for (int k = 0; k < kTotalPlanes; ++k) ge = ((c >> k) & 1) ? (t[k] & ge) : (t[k] | ge);
+    return ge;
+}
+
 __global__ __launch_bounds__(kBlock) void quorum_vote_kernel(const QuorumVoteArgs a) {
-    const size_t wi = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (wi >= a.words_total) return;
-    uint32_t n_neg[8], n_zero[8];
+    const size_t u = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (u >= a.n_vec) return;
+    u32x4 n[kCountPlanes], z[kCountPlanes];
 #pragma unroll
-    for (int n = 0; n < 8; ++n) n_neg[n] = n_zero[n] = 0;
-    for (int w = 0; w < a.M; ++w) {
-        const uint32_t zw = a.zero[w][wi];
-        const uint32_t nw = a.neg[w][wi] & ~zw;   // an abstention is not a vote, whatever the other plane says
+    for (int k = 0; k < kCountPlanes; ++k) n[k] = z[k] = splat(0u);
+    for (int w0 = 0; w0 < a.M; w0 += kQuorumBatch) {
+        u32x4 nw[kQuorumBatch], zw[kQuorumBatch];
 #pragma unroll
-        for (int n = 0; n < 8; ++n) {
-            n_neg[n] += spread_nibble((nw >> (4 * n)) & 0xFu);
-            n_zero[n] += spread_nibble((zw >> (4 * n)) & 0xFu);
-        }
+        for (int j = 0; j < kQuorumBatch; ++j)
+            if (w0 + j < a.M) {
+                nw[j] = ld_stream(reinterpret_cast<const u32x4 *>(a.neg[w0 + j]) + u);
+                zw[j] = ld_stream(reinterpret_cast<const u32x4 *>(a.zero[w0 + j]) + u);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < kQuorumBatch; ++j)
+            if (w0 + j < a.M) {
+                u32x4 cz = zw[j];
+                u32x4 cn = nw[j] & ~zw[j];   // an abstention is not a vote, whatever the other plane says
+#pragma unroll
+                for (int k = 0; k < kCountPlanes; ++k) {
+                    const u32x4 tn = n[k] & cn, tz = z[k] & cz;
+                    n[k] ^= cn;
+                    z[k] ^= cz;
+                    cn = tn;
+                    cz = tz;
+                }
+            }
     }
-    uint32_t out_neg = 0, out_zero = 0;
+    // t = 2 n + z
+    u32x4 t[kTotalPlanes];
+    t[0] = z[0];
+    u32x4 carry = splat(0u);
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t ans = quorum_answer((int)((n_neg[n] >> (8 * c)) & 0xFFu),
-                                               (int)((n_zero[n] >> (8 * c)) & 0xFFu), a.M, a.quorum);
-            out_neg |= (ans & 1u) << (4 * n + c);
-            out_zero |= ((ans >> 1) & 1u) << (4 * n + c);
-        }
+    for (int k = 1; k < kTotalPlanes; ++k) {
+        const u32x4 x = k - 1 < kCountPlanes ? n[k - 1] : splat(0u);
+        const u32x4 y = k < kCountPlanes ? z[k] : splat(0u);
+        const u32x4 xy = x ^ y;
+        t[k] = xy ^ carry;
+        carry = (x & y) | (xy & carry);
     }
-    const uint32_t live = live_mask(wi, a.d);
-    a.voted_neg[wi] = out_neg & live;
-    a.voted_zero[wi] = out_zero & live;
+    const u32x4 is_neg = planes_ge(t, a.M + a.quorum);
+    const u32x4 not_plus = planes_ge(t, a.M - a.quorum + 1);
+    u32x4 live;
+    live.x = live_mask(4 * u + 0, a.d);
+    live.y = live_mask(4 * u + 1, a.d);
+    live.z = live_mask(4 * u + 2, a.d);
+    live.w = live_mask(4 * u + 3, a.d);
+    st_stream(reinterpret_cast<u32x4 *>(a.voted_neg) + u, is_neg & live);
+    st_stream(reinterpret_cast<u32x4 *>(a.voted_zero) + u, not_plus & ~is_neg & live);
 }
 
 // ------------------------------------------------------------ apply ----

@@ -187,9 +187,11 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(const ApplyArgs a) {
 
 // ------------------------------------------------ "(good)": vote sums ----
 // Section 4's first scheme sends back the sum of the workers' signs instead of
-// its sign.  A lane owns 16 consecutive coordinates (half a packed word) so
-// that its 16 int8 sums leave as one 128-bit store; the count of "-" votes is
-// kept in byte lanes of four registers.
+// its sign.  A lane owns runs of 16 consecutive coordinates (half a packed
+// word each) so that the 16 int8 sums of a run leave as one 128-bit store and a
+// wave's stores are contiguous; the counts of "-" votes sit in byte lanes of
+// four registers per run.  The words of a batch of workers are loaded before
+// any of them is used.
 
 struct VoteSumArgs {
     const uint32_t *packed[64];
@@ -199,28 +201,57 @@ struct VoteSumArgs {
     size_t n_halves;   // ceil(d / 16)
 };
 
+constexpr int kVoteSumRows = 4;    // half-words per lane (each kBlock half-words apart)
+constexpr int kVoteSumBatch = 8;   // workers whose words are loaded together
+
 __global__ __launch_bounds__(kBlock) void vote_sum_kernel(const VoteSumArgs a) {
-    const size_t h = (size_t)blockIdx.x * kBlock + threadIdx.x;
-    if (h >= a.n_halves) return;
-    uint32_t counts[4] = {0, 0, 0, 0};
-    const unsigned shift = (unsigned)(h & 1) * 16u;
-    for (int w = 0; w < a.M; ++w) {
-        const uint32_t bits = (a.packed[w][h >> 1] >> shift) & 0xFFFFu;
+    constexpr int R = kVoteSumRows;
+    size_t h[R];
+    bool live[R];
+    uint32_t counts[R][4];
 #pragma unroll
-        for (int n = 0; n < 4; ++n) counts[n] += spread_nibble((bits >> (4 * n)) & 0xFu);
+    for (int r = 0; r < R; ++r) {
+        h[r] = ((size_t)blockIdx.x * R + r) * kBlock + threadIdx.x;
+        live[r] = h[r] < a.n_halves;
+#pragma unroll
+        for (int n = 0; n < 4; ++n) counts[r][n] = 0;
     }
-    u32x4 out;
-    out.x = sums_word(counts[0], a.M);
-    out.y = sums_word(counts[1], a.M);
-    out.z = sums_word(counts[2], a.M);
-    out.w = sums_word(counts[3], a.M);
-    const size_t first = h * 16;
-    if (first + 16 <= a.d) {
-        st_stream(reinterpret_cast<u32x4 *>(a.sums + first), out);
-    } else {
-        const uint32_t words[4] = {out.x, out.y, out.z, out.w};
-        for (size_t i = first; i < a.d; ++i)
-            a.sums[i] = (int8_t)(words[(i - first) >> 2] >> (8 * ((i - first) & 3)));
+    for (int w0 = 0; w0 < a.M; w0 += kVoteSumBatch) {
+        uint32_t word[kVoteSumBatch][R];
+#pragma unroll
+        for (int j = 0; j < kVoteSumBatch; ++j)
+            if (w0 + j < a.M) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) word[j][r] = live[r] ? a.packed[w0 + j][h[r] >> 1] : 0u;   // two lanes share a word
+            }
+        __builtin_amdgcn_sched_barrier(0);   // the batch's loads are all in flight before the first is used
+#pragma unroll
+        for (int j = 0; j < kVoteSumBatch; ++j)
+            if (w0 + j < a.M) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const uint32_t bits = (word[j][r] >> ((unsigned)(h[r] & 1) * 16u)) & 0xFFFFu;
+#pragma unroll
+                    for (int n = 0; n < 4; ++n) counts[r][n] += spread_nibble((bits >> (4 * n)) & 0xFu);
+                }
+            }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (!live[r]) continue;
+        u32x4 out;
+        out.x = sums_word(counts[r][0], a.M);
+        out.y = sums_word(counts[r][1], a.M);
+        out.z = sums_word(counts[r][2], a.M);
+        out.w = sums_word(counts[r][3], a.M);
+        const size_t first = h[r] * 16;
+        if (first + 16 <= a.d) {
+            st_stream(reinterpret_cast<u32x4 *>(a.sums + first), out);
+        } else {
+            const uint32_t words[4] = {out.x, out.y, out.z, out.w};
+            for (size_t i = first; i < a.d; ++i)
+                a.sums[i] = (int8_t)(words[(i - first) >> 2] >> (8 * ((i - first) & 3)));
+        }
     }
 }
 
@@ -263,15 +294,21 @@ __global__ __launch_bounds__(kBlock) void sum_apply_kernel(const SumApplyArgs a)
 
 // ---------------------------------------------------------------- copy ----
 
-__global__ __launch_bounds__(kBlock) void copy_kernel(f32x4 *dst, const f32x4 *src, size_t n_vec) {
+struct CopyArgs {
+    f32x4 *dst;
+    const f32x4 *src;
+    size_t n_vec;
+};
+
+__global__ __launch_bounds__(kBlock) void copy_kernel(const CopyArgs a) {
     const size_t base = (size_t)blockIdx.x * (kBlock * 4) + threadIdx.x;
     f32x4 v[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r)
-        if (base + r * kBlock < n_vec) v[r] = ld_stream(src + base + r * kBlock);
+        if (base + r * kBlock < a.n_vec) v[r] = ld_stream(a.src + base + r * kBlock);
 #pragma unroll
     for (int r = 0; r < 4; ++r)
-        if (base + r * kBlock < n_vec) st_stream(dst + base + r * kBlock, v[r]);
+        if (base + r * kBlock < a.n_vec) st_stream(a.dst + base + r * kBlock, v[r]);
 }
 
 }  // namespace ss

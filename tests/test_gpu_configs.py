@@ -2,14 +2,17 @@
 configuration bench.py times (fused ss_signum_vote_step).
 
 Two kinds of check per step:
-  * against the CPU oracle, bit for bit, on whole chunks of coordinates (all of
-    them for C1-C3; the first, the last ragged one and a few seeded ones for
-    C4 and C5).  Coordinates do not interact, so the oracle can follow a chunk
-    through every step on its own.
-  * on EVERY coordinate, properties that hold at any size, evaluated with plain
-    torch operations on the device: each worker's bit is [m_w < 0], the voted
-    bit is [2 * (number of "-" workers) > M], and x moved by exactly -delta or
-    +delta according to its voted bit (rounded once); padding bits are zero.
+  * against the CPU oracle, bit for bit, on EVERY coordinate of all five
+    workloads: voted bits, every worker's packed bits (on the steps that ask
+    for them), every momentum buffer and x, after every step.  Coordinates do
+    not interact, so the oracle follows the vector chunk by chunk; its state
+    (all momentum buffers and x) lives in host memory, the chunks travel
+    through pinned staging buffers.
+  * again on every coordinate, properties that hold at any size, evaluated
+    with plain torch operations on the device: each worker's bit is [m_w < 0],
+    the voted bit is [2 * (number of "-" workers) > M], and x moved by exactly
+    -delta or +delta according to its voted bit (rounded once); padding bits
+    are zero.
 """
 import numpy as np
 import pytest
@@ -44,7 +47,35 @@ def fill_gradients(cfg, step, g, mus, ties):
             g[w][lo:hi] = synth.grad_chunk(cfg, step, w, c, DEV, mu=mu, tie=tie)
 
 
-def run_config(ss, oracle, cfg, oracle_chunks, threads=16):
+class Staging:
+    """pinned host buffers one chunk long, reused for every device -> host copy"""
+
+    def __init__(self, M, gdtype, has_m):
+        n, nw = synth.CHUNK, synth.CHUNK // 32 + 4
+        pin = lambda *shape, dtype: torch.empty(*shape, dtype=dtype, pin_memory=True)
+        self.g = [pin(n, dtype=gdtype) for _ in range(M)]
+        self.m = [pin(n, dtype=torch.float32) for _ in range(M)] if has_m else None
+        self.x = pin(n, dtype=torch.float32)
+        self.voted = pin(nw, dtype=torch.int32)
+        self.packed = [pin(nw, dtype=torch.int32) for _ in range(M)]
+
+    @staticmethod
+    def fetch(stage, dev):
+        out = stage[:dev.numel()]
+        out.copy_(dev, non_blocking=True)
+        return out
+
+
+def host_view(t):
+    """numpy view of a (pinned) host tensor in the oracle's conventions"""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    if t.dtype == torch.int32:
+        return t.numpy().view(np.uint32)
+    return t.numpy()
+
+
+def run_config(ss, oracle, cfg, oracle_chunks, threads=16, three_calls=False):
     d, M = cfg.d, cfg.M
     has_m = cfg.beta is not None
     beta = cfg.beta if has_m else 0.0
@@ -70,6 +101,7 @@ def run_config(ss, oracle, cfg, oracle_chunks, threads=16):
         lo, hi = cfg.chunk_range(c)
         host[c] = {"m": [np.zeros(hi - lo, np.float32) for _ in range(M)] if has_m else None,
                    "x": x[lo:hi].cpu().numpy().copy()}
+    stage = Staging(M, gdtype, has_m)
 
     delta_t = torch.tensor(cfg.delta, dtype=torch.float32, device=DEV)
     forced_ties_seen = 0
@@ -82,7 +114,15 @@ def run_config(ss, oracle, cfg, oracle_chunks, threads=16):
             for p in packed:
                 p.fill_(-1)
         print("step", k, cfg.name, "packed_out" if with_packed else "voted only", flush=True)
-        ss.signum_vote_step(g, m, beta, cfg.delta, x, voted, packed if with_packed else None)
+        if three_calls:
+            # the same step as M + 2 library calls: pack per worker, vote, apply
+            with_packed = True
+            for w in range(M):
+                ss.signum_pack(g[w], m[w] if has_m else None, beta, packed[w])
+            ss.majority_vote(packed, voted, d)
+            ss.sign_apply(x, voted, cfg.delta)
+        else:
+            ss.signum_vote_step(g, m, beta, cfg.delta, x, voted, packed if with_packed else None)
         torch.cuda.synchronize()
 
         # ---- every coordinate: internal consistency on the device
@@ -117,24 +157,27 @@ def run_config(ss, oracle, cfg, oracle_chunks, threads=16):
         # ---- followed chunks: bit-exact against the oracle
         for c in oracle_chunks:
             lo, hi = cfg.chunk_range(c)
-            n = hi - lo
             st = host[c]
-            gh = [synth.as_numpy(g[w][lo:hi]) for w in range(M)]
+            gh = [host_view(stage.fetch(stage.g[w], g[w][lo:hi])) for w in range(M)]
+            torch.cuda.synchronize()
             want_voted, want_packed = oracle.signum_vote_step(gh, st["m"], beta, cfg.delta, st["x"],
                                                               want_packed=True, threads=threads)
             nw = len(want_voted)
-            got = voted[lo // 32: lo // 32 + nw].cpu().numpy().view(np.uint32)
-            assert np.array_equal(got, want_voted), ("oracle voted", k, c)
+            wlo = lo // 32
+            got_voted = host_view(stage.fetch(stage.voted, voted[wlo: wlo + nw]))
+            got_x = host_view(stage.fetch(stage.x, x[lo:hi]))
+            got_m = [host_view(stage.fetch(stage.m[w], m[w][lo:hi])) for w in range(M)] if has_m else None
+            got_packed = [host_view(stage.fetch(stage.packed[w], packed[w][wlo: wlo + nw])) for w in range(M)] \
+                if with_packed else None
+            torch.cuda.synchronize()
+            assert np.array_equal(got_voted, want_voted), ("oracle voted", k, c)
             if with_packed:
                 for w in range(M):
-                    got = packed[w][lo // 32: lo // 32 + nw].cpu().numpy().view(np.uint32)
-                    assert np.array_equal(got, want_packed[w]), ("oracle packed", k, c, w)
+                    assert np.array_equal(got_packed[w], want_packed[w]), ("oracle packed", k, c, w)
             if has_m:
                 for w in range(M):
-                    assert np.array_equal(m[w][lo:hi].cpu().numpy().view(np.uint32),
-                                          st["m"][w].view(np.uint32)), ("oracle m", k, c, w)
-            assert np.array_equal(x[lo:hi].cpu().numpy().view(np.uint32), st["x"].view(np.uint32)), \
-                ("oracle x", k, c)
+                    assert np.array_equal(got_m[w].view(np.uint32), st["m"][w].view(np.uint32)), ("oracle m", k, c, w)
+            assert np.array_equal(got_x.view(np.uint32), st["x"].view(np.uint32)), ("oracle x", k, c)
     if ties is not None:
         assert forced_ties_seen > 0.08 * d * cfg.steps
     del g, m, x, x_before, packed, voted
@@ -161,13 +204,19 @@ def test_c3_signum_vote_headline_every_coordinate(ss, oracle):
     run_config(ss, oracle, synth.C3, list(range(synth.C3.n_chunks)))
 
 
-def test_c4_even_m_ties_full_size(ss, oracle):
-    run_config(ss, oracle, synth.C4, sampled_chunks(synth.C4))
+def test_c3_three_call_path_every_coordinate(ss, oracle):
+    # the benchmark's "3-kernel path" at the headline size: M x ss_signum_pack,
+    # ss_majority_vote, ss_sign_apply, every output of every call against the oracle
+    run_config(ss, oracle, synth.C3.scaled(d=synth.C3.d, steps=6), list(range(synth.C3.n_chunks)), three_calls=True)
 
 
-def test_c5_bf16_large_full_size(ss, oracle):
+def test_c4_even_m_ties_every_coordinate(ss, oracle):
+    run_config(ss, oracle, synth.C4, list(range(synth.C4.n_chunks)))
+
+
+def test_c5_bf16_large_every_coordinate(ss, oracle):
     assert synth.C5.d % 32 == 17 and synth.C5.d % 4 == 1
-    run_config(ss, oracle, synth.C5, sampled_chunks(synth.C5, extra=2))
+    run_config(ss, oracle, synth.C5, list(range(synth.C5.n_chunks)))
 
 
 def test_c3_variants_full_size(ss, oracle):
@@ -260,8 +309,9 @@ def test_c3_variants_full_size(ss, oracle):
         assert np.array_equal(sigma[lo:hi].cpu().numpy().view(np.uint32),
                               oracle.welford_sigma(hw[c][1], M).view(np.uint32))
     out = torch.empty(3, dtype=torch.float64, device=DEV)
+    ws = ss.new_density_workspace(DEV)
     for vec in (mean, sigma):
-        ss.density(vec, out)
+        ss.density(vec, out, ws)
         want = oracle.density(vec.cpu().numpy())
         got = out.cpu().numpy()
         assert got[0] == pytest.approx(want[0], rel=1e-12) and got[1] == pytest.approx(want[1], rel=1e-12)

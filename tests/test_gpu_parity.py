@@ -224,6 +224,117 @@ def test_fused_equals_three_call_path(ss):
     assert torch.equal(vq, vf) and torch.equal(xq.view(torch.int32), xf.view(torch.int32))
 
 
+@pytest.mark.parametrize("M,dtype", [(7, "f32"), (16, "f32"), (8, "bf16")])
+def test_fused_equals_three_call_path_streaming_shape(ss, M, dtype):
+    # d >= 2^20, M >= 2: the fused call takes the streaming launch shape that the
+    # benchmark times; its outputs must be those of M packs + vote + apply, both with
+    # and without per-worker bits (ragged d, so the scalar tail takes part)
+    d = 3 * (1 << 20) + 2048 + 77
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(100 + M)
+    gdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    g = [torch.randn(d, device=DEV, generator=gen).to(gdt) for _ in range(M)]
+    m0 = [torch.randn(d, device=DEV, generator=gen) * 0.2 for _ in range(M)]
+    x0 = torch.randn(d, device=DEV, generator=gen) * 0.05
+    m3 = [t.clone() for t in m0]
+    x3 = x0.clone()
+    p3 = [dirty_bits(ss, d) for _ in range(M)]
+    for w in range(M):
+        ss.signum_pack(g[w], m3[w], 0.9, p3[w])
+    v3 = dirty_bits(ss, d)
+    ss.majority_vote(p3, v3, d)
+    ss.sign_apply(x3, v3, 1e-4)
+    for with_packed in (True, False):
+        mf = [t.clone() for t in m0]
+        xf = x0.clone()
+        vf = dirty_bits(ss, d)
+        pf = [dirty_bits(ss, d) for _ in range(M)] if with_packed else None
+        ss.signum_vote_step(g, mf, 0.9, 1e-4, xf, vf, pf)
+        torch.cuda.synchronize()
+        assert torch.equal(vf, v3) and torch.equal(xf.view(torch.int32), x3.view(torch.int32))
+        for w in range(M):
+            assert torch.equal(mf[w].view(torch.int32), m3[w].view(torch.int32)), w
+            if with_packed:
+                assert torch.equal(pf[w], p3[w]), w
+
+
+def test_nan_and_inf_follow_the_sign_rule(ss, oracle):
+    # "bit = (v < 0)" applied literally: NaN is "+", -Inf is "-", +Inf is "+".  Packed and voted
+    # bits and x are compared with the oracle exactly; momentum exactly wherever it is not a NaN
+    # (a NaN's payload is not part of the contract), and NaN where the oracle's is NaN.
+    M, d = 5, 8192 + 333
+    rng = np.random.default_rng(77)
+    nan, inf = np.float32("nan"), np.float32("inf")
+    g = [(rng.standard_normal(d)).astype(np.float32) for _ in range(M)]
+    m = [(rng.standard_normal(d) * 0.3).astype(np.float32) for _ in range(M)]
+    x = (rng.standard_normal(d) * 0.05).astype(np.float32)
+    for w in range(M):
+        idx = rng.permutation(d)[:600]
+        g[w][idx[:100]] = nan
+        g[w][idx[100:200]] = inf
+        g[w][idx[200:300]] = -inf
+        m[w][idx[300:400]] = nan
+        m[w][idx[400:500]] = inf
+        m[w][idx[500:600]] = -inf
+    m[0][:64] = inf
+    g[0][:64] = -inf            # inf - inf = NaN inside the update
+    for momentum in (True, False):
+        g_dev = [torch.from_numpy(a).to(DEV) for a in g]
+        m_dev = [torch.from_numpy(a.copy()).to(DEV) for a in m] if momentum else None
+        m_host = [a.copy() for a in m] if momentum else None
+        x_dev, x_host = torch.from_numpy(x.copy()).to(DEV), x.copy()
+        voted = dirty_bits(ss, d)
+        packed = [dirty_bits(ss, d) for _ in range(M)]
+        ss.signum_vote_step(g_dev, m_dev, 0.9, 1e-3, x_dev, voted, packed)
+        want_voted, want_packed = oracle.signum_vote_step(g, m_host, 0.9, 1e-3, x_host, want_packed=True)
+        assert np.array_equal(bits_np(voted), want_voted)
+        for w in range(M):
+            assert np.array_equal(bits_np(packed[w]), want_packed[w]), w
+        assert_same_floats(x_dev, x_host, "x")
+        if momentum:
+            for w in range(M):
+                got = m_dev[w].cpu().numpy()
+                isn = np.isnan(m_host[w])
+                assert np.array_equal(np.isnan(got), isn), w
+                assert isn.sum() >= 200
+                assert np.array_equal(got.view(np.uint32)[~isn], m_host[w].view(np.uint32)[~isn]), w
+        # the stand-alone pack on the same inputs
+        for w in range(M):
+            p = dirty_bits(ss, d)
+            mm = torch.from_numpy(m[w].copy()).to(DEV) if momentum else None
+            ss.signum_pack(g_dev[w], mm, 0.9, p)
+            assert np.array_equal(bits_np(p), want_packed[w]), w
+
+
+def test_inputs_that_are_only_read_may_coincide(ss, oracle):
+    # one gradient handed in for several workers, one packed buffer handed in for several
+    # voters: allowed (nothing is written there) and equal to separate copies
+    d = 70_001
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(9)
+    g = torch.randn(d, device=DEV, generator=gen)
+    x0 = torch.randn(d, device=DEV, generator=gen) * 0.05
+    xa, xb = x0.clone(), x0.clone()
+    va, vb = dirty_bits(ss, d), dirty_bits(ss, d)
+    ss.signum_vote_step([g, g, g], None, 0.0, 1e-3, xa, va)
+    ss.signum_vote_step([g, g.clone(), g.clone()], None, 0.0, 1e-3, xb, vb)
+    assert torch.equal(va, vb) and torch.equal(xa.view(torch.int32), xb.view(torch.int32))
+    p = dirty_bits(ss, d)
+    ss.signum_pack(g, None, 0.0, p)
+    assert torch.equal(p, va)                       # three identical voters: the vote is their sign
+    v2 = dirty_bits(ss, d)
+    ss.majority_vote([p, p, p, p], v2, d)
+    assert torch.equal(v2, p)
+    # a bf16 gradient is half as long: a buffer that starts right behind it is clear of it
+    gb = torch.randn(2 * d + 64, device=DEV, generator=gen).to(torch.bfloat16)
+    packed = dirty_bits(ss, d)
+    ss.signum_pack(gb, None, 0.0, packed, d=d)
+    assert np.array_equal(bits_np(packed), oracle.signum_pack(synth.as_numpy(gb[:d]), None, 0.0))
+    # ... and a written buffer that does touch an input is refused
+    with pytest.raises(ss.SignSGDError):
+        ss.signum_vote_step([g, g], [g, torch.zeros(d, device=DEV)], 0.9, 1e-3, xa, va)
+
+
 def test_subnormals_are_not_flushed(ss, oracle):
     # products that underflow into the subnormal range, and subnormal inputs:
     # the device must keep them (a flush would turn "-" votes into "+")

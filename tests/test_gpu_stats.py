@@ -12,11 +12,14 @@ from test_gpu_parity import DEV, RAGGED, assert_same_floats
 
 pytestmark = pytest.mark.gpu
 
-# Both sums add exact, non-negative fp64 terms.  A lane adds at most
-# d / (8192 blocks * 256 lanes) + 32 terms one after the other, then at most
-# 6 + 2 + 13 more additions combine lanes, waves and blocks: with d = 1.5e9
-# that is under 800 roundings of relative size 2^-53 each, i.e. < 1e-13.  The
-# oracle accumulates in 80-bit long double (< 1e-10 * 2^-11 of the sum).
+# Both sums add exact, non-negative fp64 terms, so every rounding error has the
+# same sign bound: relative error <= (number of additions on the longest chain)
+# * 2^-53.  A lane adds at most ceil(d / (8192 * G)) * 32 + d / (256 * G) + 1
+# terms one after the other (G <= 1024 blocks, at least half of that once
+# d >= 2^23), then 6 + 3 additions combine lanes and waves, and the last block
+# adds at most 4 + 6 + 3 more: for d <= 2^31 that is under 2^14 + 64 roundings of
+# 2^-53 each, < 1e-12 - the sizes tested here stay far below it.  The oracle
+# accumulates in 80-bit long double (its own error is 2^-11 of that).
 DENSITY_RTOL = 1e-12
 
 
@@ -54,12 +57,18 @@ def test_welford_update_and_sigma(ss, oracle, d, dtype):
     assert_same_floats(sigma_dev, oracle.welford_sigma(m2, 5), "sigma")
 
 
+@pytest.fixture(scope="module")
+def ws(ss):
+    # one workspace for the whole module: every call must leave it ready for the next
+    return ss.new_density_workspace(DEV)
+
+
 @pytest.mark.parametrize("d", [0] + RAGGED + [9_000_011])
-def test_density(ss, oracle, d):
+def test_density(ss, oracle, ws, d):
     rng = np.random.default_rng(d + 1)
     v = (rng.standard_normal(d) * 10.0 ** rng.integers(-3, 3, d)).astype(np.float32)
     out = torch.full((3,), -1.0, dtype=torch.float64, device=DEV)
-    ss.density(torch.from_numpy(v).to(DEV) if d else torch.zeros(4, device=DEV), out, d=d)
+    ss.density(torch.from_numpy(v).to(DEV) if d else torch.zeros(4, device=DEV), out, ws, d=d)
     got = out.cpu().numpy()
     want = oracle.density(v)
     assert got[0] == pytest.approx(want[0], rel=DENSITY_RTOL)
@@ -67,20 +76,40 @@ def test_density(ss, oracle, d):
     assert got[2] == pytest.approx(want[2], rel=3 * DENSITY_RTOL)
 
 
-def test_density_special_vectors(ss):
+def test_density_is_the_same_bits_on_every_run(ss, ws):
+    # the order of every addition depends on d alone: repeated runs, runs after a
+    # call of another size on the same workspace, and a fresh workspace all agree
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(11)
+    for d in (1, 4099, 1_300_007, 25_557_032):
+        v = torch.randn(d, device=DEV, generator=gen) * 3.0
+        outs = []
+        for rep in range(6):
+            out = torch.full((3,), -1.0, dtype=torch.float64, device=DEV)
+            if rep == 3:      # another size in between
+                ss.density(v, out, ws, d=max(1, d // 3))
+            work = ss.new_density_workspace(DEV) if rep == 5 else ws
+            ss.density(v, out, work)
+            outs.append(out.cpu().numpy().view(np.uint64).copy())
+        for o in outs[1:]:
+            assert np.array_equal(o, outs[0]), d
+        assert int(ws[0]) == 0                                   # the ticket is back at zero
+
+
+def test_density_special_vectors(ss, ws):
     out = torch.empty(3, dtype=torch.float64, device=DEV)
     d = 5_000_001
-    ss.density(torch.full((d,), -2.5, device=DEV), out)
+    ss.density(torch.full((d,), -2.5, device=DEV), out, ws)
     assert out.cpu().tolist() == [2.5 * d, 6.25 * d, 1.0]                       # fully dense
     hot = torch.zeros(d, device=DEV)
     hot[d - 1] = 3.0
-    ss.density(hot, out)
+    ss.density(hot, out, ws)
     assert out.cpu().tolist() == [3.0, 9.0, 9.0 / (d * 9.0)]                   # one-hot: 1/d
-    ss.density(torch.zeros(d, device=DEV), out)
+    ss.density(torch.zeros(d, device=DEV), out, ws)
     assert out.cpu().tolist() == [0.0, 0.0, 0.0]
 
 
-def test_gradient_and_noise_density_of_a_synthetic_run(ss, oracle):
+def test_gradient_and_noise_density_of_a_synthetic_run(ss, oracle, ws):
     # what Figure 1 measures, on the C3 recipe: Welford over K stochastic
     # gradients of one worker, then phi(mean) and phi(sigma).  The mean of
     # Gaussian gradients around a Gaussian mu is Gaussian: phi -> 2/pi; sigma
@@ -100,10 +129,10 @@ def test_gradient_and_noise_density_of_a_synthetic_run(ss, oracle):
     sigma = torch.empty_like(m2)
     ss.welford_sigma(m2, K, sigma)
     out = torch.empty(3, dtype=torch.float64, device=DEV)
-    ss.density(mean, out)
+    ss.density(mean, out, ws)
     phi_g = float(out[2])
     assert phi_g == pytest.approx(oracle.density(mean_h)[2], rel=3 * DENSITY_RTOL)
-    ss.density(sigma, out)
+    ss.density(sigma, out, ws)
     phi_s = float(out[2])
     assert phi_s == pytest.approx(oracle.density(oracle.welford_sigma(m2_h, K))[2], rel=3 * DENSITY_RTOL)
     nu = K - 1

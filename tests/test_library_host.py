@@ -106,6 +106,66 @@ def test_warmup_length_matches_the_paper_and_the_oracle(lib, oracle):
         assert lib.ss_warmup_length(beta) == oracle.warmup_length(beta)
     for beta in (0.0, 1.0, -1.0, 2.0, float("nan")):
         assert lib.ss_warmup_length(beta) == -5
+    # the search is bounded: a beta so close to 1 that C would exceed the documented
+    # maximum comes back as SS_ERR_RANGE (distinct from an invalid beta) after a bounded time
+    import time
+    t0 = time.perf_counter()
+    assert lib.ss_warmup_length(1.0 - 2.0 ** -24) == -7
+    assert lib.ss_warmup_length(0.9999999) == -7
+    assert time.perf_counter() - t0 < 2.0
+    assert lib.ss_warmup_length(0.9999) == oracle.warmup_length(0.9999) > 100_000
+
+
+def test_a_written_buffer_may_not_overlap_any_other(lib):
+    """No kernel is launched: the overlap check comes after the NULL / alignment
+    checks and before the launch, and the pointers here are not device memory."""
+    ARG = -5
+    vp = ctypes.c_void_p
+    d = 1024                                   # 4096 bytes of fp32, 128 bytes of packed bits
+    g, m, x, bits, out = 0x100000, 0x200000, 0x300000, 0x400000, 0x500000
+    one = lambda p: (vp * 1)(p)
+    two = lambda p, q: (vp * 2)(p, q)
+    f = ctypes.c_float
+    # ss_signum_pack: m inside g, packed inside m, exact alias, last byte only
+    assert lib.ss_signum_pack(vp(g), 0, vp(g + 16), f(0.9), vp(bits), d, None) == ARG
+    assert lib.ss_signum_pack(vp(g), 0, vp(m), f(0.9), vp(m + 4080), d, None) == ARG
+    assert lib.ss_signum_pack(vp(g), 0, vp(g), f(0.9), vp(bits), d, None) == ARG
+    assert lib.ss_signum_pack(vp(g), 0, None, f(0.9), vp(g + 4080), d, None) == ARG
+    # bf16 gradients are half as long: the same offset is now clear of g ...
+    # (validation passes, so do not run this one - it would launch; checked on the GPU instead)
+    # ss_majority_vote: voted aliases an input; two inputs may coincide (read only) - that
+    # case passes validation and would launch, so it is exercised in the GPU tests
+    assert lib.ss_majority_vote(two(bits, bits + 0x1000), 2, vp(bits + 0x1000), d, None) == ARG
+    assert lib.ss_majority_vote(two(bits, bits + 0x1000), 2, vp(bits + 112), d, None) == ARG
+    # ss_sign_apply
+    assert lib.ss_sign_apply(vp(x), vp(x + 2048), f(0.1), d, None) == ARG
+    # the fused step: every written buffer against everything else
+    step = lib.ss_signum_vote_step
+    ok_g, ok_m = two(g, g + 0x10000), two(m, m + 0x10000)
+    assert step(ok_g, 0, two(m, m + 2048), 2, f(0.9), f(0.1), vp(x), vp(bits), None, d, None) == ARG      # m0 / m1
+    assert step(ok_g, 0, two(m, g + 0x10000), 2, f(0.9), f(0.1), vp(x), vp(bits), None, d, None) == ARG  # m1 == g1
+    assert step(ok_g, 0, ok_m, 2, f(0.9), f(0.1), vp(m + 0x10000 + 4000), vp(bits), None, d, None) == ARG  # x / m1
+    assert step(ok_g, 0, ok_m, 2, f(0.9), f(0.1), vp(x), vp(x + 4080), None, d, None) == ARG              # voted / x
+    assert step(ok_g, 0, ok_m, 2, f(0.9), f(0.1), vp(x), vp(bits), two(out, bits), d, None) == ARG        # packed_out1 == voted
+    assert step(ok_g, 0, None, 2, f(0.9), f(0.1), vp(g + 0x10000), vp(bits), None, d, None) == ARG        # x == g1
+    ex = lib.ss_signum_vote_step_ex
+    assert ex(ok_g, 0, ok_m, 2, f(0.9), f(0.1), vp(x), vp(bits), None, vp(x + 4000), d, 2, None) == ARG    # sums / x
+    # the "(good)" pair, Welford, the ternary calls and the copy
+    assert lib.ss_vote_sum(two(bits, bits + 0x1000), 2, vp(bits + 0x1000 + 64), d, None) == ARG
+    assert lib.ss_sum_apply(vp(x), vp(x + 1024), f(0.1), d, None) == ARG
+    u64 = ctypes.c_uint64
+    assert lib.ss_welford_update(vp(g), 0, vp(m), vp(m + 16), u64(1), d, None) == ARG
+    assert lib.ss_welford_update(vp(g), 0, vp(g), vp(m), u64(1), d, None) == ARG
+    assert lib.ss_welford_sigma(vp(m), u64(2), vp(m), d, None) == ARG
+    assert lib.ss_signum_pack_ternary(vp(g), 0, None, f(0.9), f(0.1), vp(bits), vp(bits + 64), d, None) == ARG
+    assert lib.ss_quorum_vote(one(bits), one(bits + 0x1000), 1, 1, vp(out), vp(out + 16), d, None) == ARG
+    assert lib.ss_quorum_vote(one(bits), one(bits + 0x1000), 1, 1, vp(out), vp(bits + 0x1000), d, None) == ARG
+    assert lib.ss_ternary_apply(vp(x), vp(bits), vp(x + 4000), f(0.1), d, None) == ARG
+    tstep = lib.ss_signum_vote_step_ternary
+    assert tstep(ok_g, 0, ok_m, 2, f(0.9), f(0.1), 1, f(0.1), vp(x), vp(bits), vp(bits + 96), d, None) == ARG
+    assert tstep(ok_g, 0, two(m, m), 2, f(0.9), f(0.1), 1, f(0.1), vp(x), vp(bits), vp(out), d, None) == ARG
+    assert lib.ss_stream_copy(vp(x), vp(x + 1024), 4096, None) == ARG
+    assert lib.ss_last_hip_error() == 0
 
 
 def test_variant_entry_points_validate_arguments(lib):
@@ -140,9 +200,16 @@ def test_statistics_entry_points_validate_arguments(lib):
     assert lib.ss_welford_sigma(a, u64(0), a, 8, None) == -5
     assert lib.ss_welford_sigma(None, u64(2), a, 8, None) == -1
     assert lib.ss_welford_sigma(a, u64(2), odd, 8, None) == -3
-    assert lib.ss_density(a, 8, None, None) == -1
-    assert lib.ss_density(None, 8, a, None) == -1
-    assert lib.ss_density(a, 8, odd, None) == -3
+    b, c = ctypes.c_void_p(0x2000), ctypes.c_void_p(0x9000)
+    lib.ss_density_workspace_bytes.restype = ctypes.c_size_t
+    wsb = lib.ss_density_workspace_bytes()
+    assert wsb % 16 == 0 and 1024 <= wsb <= 64 * 1024
+    assert lib.ss_density(a, 8, None, c, None) == -1
+    assert lib.ss_density(None, 8, b, c, None) == -1
+    assert lib.ss_density(a, 8, b, None, None) == -1
+    assert lib.ss_density(a, 8, odd, c, None) == -3
+    assert lib.ss_density(a, 8, b, odd, None) == -3
+    assert lib.ss_density(a, 8, c, c, None) == -5                       # out inside the workspace
 
 
 def test_abstention_entry_points_validate_arguments(lib):

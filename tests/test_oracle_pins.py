@@ -448,6 +448,34 @@ def test_step_equals_three_calls_and_threaded_split(oracle, gdt):
         assert all(np.array_equal(a, b) for a, b in zip(pf, p3))
 
 
+@pytest.mark.parametrize("d", [1, 31, 4_099, 262_144 + 33, 1_300_007])
+@pytest.mark.parametrize("gdt,momentum", [("f32", True), ("bf16", True), ("f32", False)])
+def test_threaded_wrapper_equals_the_scalar_routine(oracle, d, gdt, momentum):
+    """The large GPU tests use the threaded wrapper with 16 threads as their reference: it must
+    return exactly what the scalar routine (the one the pins above hold) returns, whatever the
+    thread count and wherever the cuts between threads fall (sizes below, at and far above one
+    word per thread; more threads than words)."""
+    rng = np.random.default_rng(d)
+    M = 4
+    if gdt == "f32":
+        g = [rng.standard_normal(d).astype(np.float32) for _ in range(M)]
+    else:
+        g = [(rng.standard_normal(d).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16) for _ in range(M)]
+    m0 = [rng.standard_normal(d).astype(np.float32) * np.float32(0.2) for _ in range(M)] if momentum else None
+    x0 = rng.standard_normal(d).astype(np.float32)
+    m1 = [a.copy() for a in m0] if momentum else None
+    x1 = x0.copy()
+    v1, p1 = oracle.signum_vote_step(g, m1, 0.9, 1e-3, x1, want_packed=True, threads=1)
+    for threads in (2, 16, 64):
+        mt = [a.copy() for a in m0] if momentum else None
+        xt = x0.copy()
+        vt, pt = oracle.signum_vote_step(g, mt, 0.9, 1e-3, xt, want_packed=True, threads=threads)
+        assert np.array_equal(vt, v1) and np.array_equal(xt.view(np.uint32), x1.view(np.uint32)), threads
+        assert all(np.array_equal(a, b) for a, b in zip(pt, p1)), threads
+        if momentum:
+            assert all(np.array_equal(a.view(np.uint32), b.view(np.uint32)) for a, b in zip(mt, m1)), threads
+
+
 def test_empty_input_is_a_no_op(oracle):
     e = np.empty(0, dtype=np.float32)
     assert oracle.packed_words(0) == 0 and oracle.packed_bytes(0) == 0
