@@ -275,6 +275,27 @@ int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d,
 size_t ss_density_workspace_bytes(void);
 int ss_density(const float *v, size_t d, double *out, void *workspace, void *hip_stream);
 
+/*
+ * ss_density for callers that cannot allocate device memory or hand in a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same kernel, same results bit for bit as ss_density; the
+ * partial sums live in a fixed array inside the library instead
+ * (ss_density_workspace_bytes() bytes = 16,448, one copy per device, held until
+ * the process ends).  The call allocates and frees nothing.
+ *   v, out  as for ss_density
+ *   d       at most SS_DENSITY_STATIC_MAX_D coordinates, else SS_ERR_RANGE
+ * The device that is current when the call is made must be the one v and out
+ * live on.  All calls on one device share that device's array: calls that may
+ * overlap in time on one device (two streams, two threads) race - serialise
+ * them, or give each its own workspace through ss_density.  The first call on a
+ * device looks up the array's address (a host-side runtime query, no stream
+ * operation); make that first call outside of graph capture.  A call that is
+ * killed half-way can leave the array's counter non-zero; the process cannot
+ * repair that (ss_density with a fresh workspace still works).
+ */
+#define SS_DENSITY_STATIC_MAX_D ((size_t)1 << 36)
+int ss_density_static(const float *v, size_t d, double *out, void *hip_stream);
+
 /* the hipError_t (as int) behind this thread's most recent SS_ERR_HIP; 0 if none */
 int ss_last_hip_error(void);
 

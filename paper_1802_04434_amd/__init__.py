@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     last_hip_error, library_path, load_library, majority_vote, new_bits, packed_bytes,
     packed_words, sign_apply, signum_pack, signum_pack_warmup, signum_vote_step,
     signum_vote_step_ex, stream_copy, sum_apply, vote_sum, warmup_length,
-    density, new_density_workspace, welford_sigma, welford_update,
+    density, density_static, new_density_workspace, welford_sigma, welford_update,
     quorum_vote, signum_pack_ternary, signum_vote_step_ternary, ternary_apply,
 )

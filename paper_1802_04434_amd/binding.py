@@ -62,6 +62,8 @@ def load_library():
         L.ss_density.argtypes = [vp, sz, vp, vp, vp]
         L.ss_density_workspace_bytes.restype = sz
         L.ss_density_workspace_bytes.argtypes = []
+        L.ss_density_static.argtypes = [vp, sz, vp, vp]
+        L.ss_density_static.restype = i32
         L.ss_signum_pack_ternary.argtypes = [vp, i32, vp, f32, f32, vp, vp, sz, vp]
         L.ss_quorum_vote.argtypes = [vp, vp, i32, i32, vp, vp, sz, vp]
         L.ss_ternary_apply.argtypes = [vp, vp, vp, f32, sz, vp]
@@ -277,6 +279,15 @@ def density(v, out, workspace, d=None, stream=None):
     vp = _dev(v, torch.float32, d, "v") if d else None
     wp = _dev(workspace, torch.int64, L.ss_density_workspace_bytes() // 8, "workspace")
     _check("ss_density", L.ss_density(vp, d, _dev(out, torch.float64, 3, "out"), wp, _stream(stream)))
+    return out
+
+
+def density_static(v, out, d=None, stream=None):
+    """ss_density_static: ss_density on the library's own fixed scratch array (allocates nothing)"""
+    L = load_library()
+    d = v.numel() if d is None else d
+    vp = _dev(v, torch.float32, d, "v") if d else None
+    _check("ss_density_static", L.ss_density_static(vp, d, _dev(out, torch.float64, 3, "out"), _stream(stream)))
     return out
 
 

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "step_kernels.hpp"
@@ -12,9 +13,19 @@
 #include "stats_kernels.hpp"
 #include "ternary_kernels.hpp"
 
+// Scratch area of ss_density_static: the same layout ss_density finds in its caller's workspace,
+// one copy per device that loads this library, zero when the module is loaded and left zero
+// (ticket) by every call that runs to completion.  In host code this name only stands for the
+// symbol; the device address comes from hipGetSymbolAddress (see ss_density_static).
+static __device__ __align__(256) unsigned long long scratch[sizeof(ss::DensityScratch) / sizeof(unsigned long long)];
+
 namespace {
 
 thread_local int g_last_hip_error = 0;
+
+// device address of `scratch` on each device, looked up the first time a device is used
+constexpr int kMaxDevices = 64;
+std::atomic<ss::DensityScratch *> g_scratch_on_device[kMaxDevices];
 
 constexpr size_t kMaxGrid = 0x7FFFFFFFull;
 
@@ -541,6 +552,36 @@ int ss_density(const float *v, size_t d, double *out, void *workspace, void *hip
                      span(v, d * sizeof(float), false)};
     if (written_spans_overlap(spans, 3)) return SS_ERR_ARG;
     return density_impl(v, d, out, static_cast<ss::DensityScratch *>(workspace), static_cast<hipStream_t>(hip_stream));
+}
+
+int ss_density_static(const float *v, size_t d, double *out, void *hip_stream) {
+    if (!out) return SS_ERR_NULL;
+    if (d > 0 && !v) return SS_ERR_NULL;
+    if (!aligned16(v) || !aligned16(out)) return SS_ERR_ALIGN;
+    if (d > SS_DENSITY_STATIC_MAX_D) return SS_ERR_RANGE;
+    Span spans[2] = {span(out, 3 * sizeof(double), true), span(v, d * sizeof(float), false)};
+    if (written_spans_overlap(spans, 2)) return SS_ERR_ARG;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return SS_ERR_HIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices) return SS_ERR_ARG;
+    ss::DensityScratch *on_device = g_scratch_on_device[dev].load(std::memory_order_acquire);
+    if (!on_device) {
+        // first call on this device (which is current): every device holds its own copy of the
+        // array at its own address.  Two threads racing here look up the same address.
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            g_last_hip_error = (int)e;
+            return SS_ERR_HIP;
+        }
+        on_device = static_cast<ss::DensityScratch *>(p);
+        g_scratch_on_device[dev].store(on_device, std::memory_order_release);
+    }
+    return density_impl(v, d, out, on_device, static_cast<hipStream_t>(hip_stream));
 }
 
 // ---- majority vote with abstention ----
