@@ -31,7 +31,6 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "fused_step_C3_hbm_traffic.md")
 
 
 def library_source_digest():
@@ -44,12 +43,13 @@ def library_source_digest():
     return h.hexdigest()[:16]
 
 
-def counter_traffic():
-    """HBM bytes per launch of the fused C3 step from the committed hardware-counter
-    summary - but only if that summary was taken with exactly the sources this run
+def counter_traffic(workload):
+    """HBM bytes per launch of the fused step from the committed hardware-counter
+    summary of that workload (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the copy
+    kernel) - but only if the summary was taken with exactly the sources this run
     uses (it records their digest); otherwise None."""
     try:
-        text = open(TRAFFIC_FILE).read()
+        text = open(os.path.join(ROOT, "profiles", "fused_step_%s_profile.md" % workload)).read()
     except OSError:
         return None
     m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
@@ -272,7 +272,7 @@ def main():
                                % (cfg.name, d, cfg.grad_dtype, M, cfg.beta, cfg.delta, ENTRY_POINT[kernel])},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": counter_traffic() if (args.workload == "C3" and kernel == "fused") else None},
+                     "traffic": counter_traffic(args.workload) if kernel == "fused" else None},
         "cpu_baseline": cpu,
         "extra": extra,
     }

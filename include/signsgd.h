@@ -121,8 +121,8 @@ int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d,
  *   voted       out  ss_packed_bytes(d) bytes: the bits that were applied
  *   packed_out  out  NULL, or host array of M device pointers that receive
  *                    every worker's sign bits (ss_packed_bytes(d) bytes each)
- * Normally one kernel launch.  When packed_out is given, d >= 2^24 and there
- * are many workers (10, or 4 with bf16 gradients), the call enqueues M + 2
+ * Normally one kernel launch.  When packed_out is given, d >= 2^24, the
+ * gradients are fp32 and there are 10 workers or more, the call enqueues M + 2
  * launches that hand the signs over through packed_out, which is faster there;
  * the results are the same.  Should the runtime refuse one of those launches
  * (SS_ERR_HIP), the launches before it stay enqueued: some momentum buffers

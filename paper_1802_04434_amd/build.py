@@ -7,7 +7,6 @@ separately), packed-fp32 instructions disabled, no fast-math.
 """
 import os
 import subprocess
-import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -23,10 +22,10 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(extra_flags=(), out=LIB, verbose=False):
+def build(out=LIB, verbose=False):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = out + ".tmp%d" % os.getpid()
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-o", tmp] + [os.path.join(CSRC, s) for s in SOURCES]
+    cmd = [hipcc, *HIPCC_FLAGS, "-o", tmp] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
@@ -54,5 +53,5 @@ def build_abi_check(verbose=False):
 
 
 if __name__ == "__main__":
-    print(build(extra_flags=sys.argv[1:], verbose=True))
+    print(build(verbose=True))
     print(build_abi_check(verbose=True))

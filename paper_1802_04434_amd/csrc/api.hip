@@ -33,6 +33,13 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 inline size_t grad_bytes(ss_dtype gdt) { return gdt == SS_BF16 ? 2 : 4; }
 
+// binary digits needed for a count of up to M votes
+inline int count_planes(int M) {
+    int p = 1;
+    while ((1 << p) <= M) ++p;
+    return p;
+}
+
 // A buffer of one call, for the check that nothing that is written shares a byte
 // with anything else (buffers that are only read may coincide, e.g. one gradient
 // handed in for two workers).
@@ -104,8 +111,7 @@ constexpr int kLdsPerUnitKB = 160;   // what the reservations below assume; chec
 
 // when ss_signum_vote_step is given packed_out buffers it may run as M + 2 launches (see there)
 constexpr size_t kSplitMinD = (size_t)1 << 24;
-constexpr int kSplitMinWorkersF32 = 10;
-constexpr int kSplitMinWorkersBf16 = 4;
+constexpr int kSplitMinWorkers = 10;
 
 constexpr int latency_rows(int m, bool has_m) {
     const int streams = m * (has_m ? 2 : 1);
@@ -403,12 +409,13 @@ int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m, 
         spans[n++] = span(sums_out, d, true);
         if (written_spans_overlap(spans, n)) return SS_ERR_ARG;
     }
-    // Many workers over a large vector, and the caller wants every worker's bits anyway: then
-    // those buffers can carry the signs from launch to launch, and M pack launches + vote + apply
-    // (each touching three streams chip-wide at a time) measured 4-15 % faster than the one-pass
-    // kernel with its 2M+1 input and M+1 output streams.  Same results, bit for bit.
-    if (packed_out && !sums_out && !(flags & SS_STEP_SUM_UPDATE) && d >= kSplitMinD &&
-        M >= (gdt == SS_BF16 ? kSplitMinWorkersBf16 : kSplitMinWorkersF32)) {
+    // Many workers with fp32 gradients over a large vector, and the caller wants every worker's
+    // bits anyway: then those buffers can carry the signs from launch to launch, and M pack
+    // launches + vote + apply (each touching three streams chip-wide at a time) measured 5 %
+    // faster at M = 16 than the one-pass kernel with its 2M+1 input and M+1 output streams.  Same
+    // results, bit for bit.  (With bf16 gradients the one-pass kernel is the faster one.)
+    if (packed_out && !sums_out && !(flags & SS_STEP_SUM_UPDATE) && d >= kSplitMinD && gdt == SS_F32 &&
+        M >= kSplitMinWorkers) {
         for (int w = 0; w < M; ++w) {
             const int rc = signum_pack_impl(g[w], gdt, m ? m[w] : nullptr, beta, packed_out[w], d,
                                             flags & SS_STEP_WARMUP, hip_stream);
@@ -456,11 +463,19 @@ int ss_vote_sum(const uint32_t *const *packed, int M, int8_t *sums, size_t d, vo
     a.sums = sums;
     a.M = M;
     a.d = d;
-    a.n_halves = (d + 15) / 16;
-    const size_t per_block = (size_t)ss::kBlock * ss::kVoteSumRows;
-    const size_t grid = (a.n_halves + per_block - 1) / per_block;
+    a.n_vec = ss_packed_bytes(d) / 16;
+    const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    return launch(ss::vote_sum_kernel, grid, 0, static_cast<hipStream_t>(hip_stream), a);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    switch (count_planes(M)) {
+        case 1: return launch(ss::vote_sum_kernel<1>, grid, 0, stream, a);
+        case 2: return launch(ss::vote_sum_kernel<2>, grid, 0, stream, a);
+        case 3: return launch(ss::vote_sum_kernel<3>, grid, 0, stream, a);
+        case 4: return launch(ss::vote_sum_kernel<4>, grid, 0, stream, a);
+        case 5: return launch(ss::vote_sum_kernel<5>, grid, 0, stream, a);
+        case 6: return launch(ss::vote_sum_kernel<6>, grid, 0, stream, a);
+        default: return launch(ss::vote_sum_kernel<7>, grid, 0, stream, a);
+    }
 }
 
 int ss_sum_apply(float *x, const int8_t *sums, float delta, size_t d, void *hip_stream) {
@@ -644,7 +659,16 @@ int ss_quorum_vote(const uint32_t *const *neg, const uint32_t *const *zero, int 
     a.n_vec = ss_packed_bytes(d) / 16;
     const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    return launch(ss::quorum_vote_kernel, grid, 0, static_cast<hipStream_t>(hip_stream), a);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    switch (count_planes(M)) {
+        case 1: return launch(ss::quorum_vote_kernel<1>, grid, 0, stream, a);
+        case 2: return launch(ss::quorum_vote_kernel<2>, grid, 0, stream, a);
+        case 3: return launch(ss::quorum_vote_kernel<3>, grid, 0, stream, a);
+        case 4: return launch(ss::quorum_vote_kernel<4>, grid, 0, stream, a);
+        case 5: return launch(ss::quorum_vote_kernel<5>, grid, 0, stream, a);
+        case 6: return launch(ss::quorum_vote_kernel<6>, grid, 0, stream, a);
+        default: return launch(ss::quorum_vote_kernel<7>, grid, 0, stream, a);
+    }
 }
 
 int ss_ternary_apply(float *x, const uint32_t *neg, const uint32_t *zero, float delta, size_t d,

@@ -197,23 +197,26 @@ struct QuorumVoteArgs {
 //     answer "-"  iff  S <= -Q  iff  t >= M + Q
 //     answer  0   iff  |S| < Q  iff  M - Q < t < M + Q
 // which are two comparisons of t with constants, done from the lowest plane up.
-constexpr int kCountPlanes = 7;    // n, z <= 64
-constexpr int kTotalPlanes = 8;    // t <= 128 + 64
 constexpr int kQuorumBatch = 4;    // workers (two planes each) whose words are loaded together
 
 __device__ __forceinline__ u32x4 splat(uint32_t v) { return u32x4{v, v, v, v}; }
 
-// planes of (t >= c) for a constant c, t given by its binary planes
-__device__ __forceinline__ u32x4 planes_ge(const u32x4 (&t)[kTotalPlanes], int c) {
+// planes of (t >= c) for a constant c, t given by its N binary planes
+template <int N>
+__device__ __forceinline__ u32x4 planes_ge(const u32x4 (&t)[N], int c) {
     if (c <= 0) return splat(0xFFFFFFFFu);
-    if (c >= (1 << kTotalPlanes)) return splat(0u);
+    if (c >= (1 << N)) return splat(0u);
     u32x4 ge = splat(0xFFFFFFFFu);
 #pragma unroll
-    for (int k = 0; k < kTotalPlanes; ++k) ge = ((c >> k) & 1) ? (t[k] & ge) : (t[k] | ge);
+    for (int k = 0; k < N; ++k) ge = ((c >> k) & 1) ? (t[k] & ge) : (t[k] | ge);
     return ge;
 }
 
+// P = number of binary planes of n and z (M < 2^P); t = 2 n + z <= 2 M needs one more
+template <int P>
 __global__ __launch_bounds__(kBlock) void quorum_vote_kernel(const QuorumVoteArgs a) {
+    constexpr int kCountPlanes = P;
+    constexpr int kTotalPlanes = P + 1;
     const size_t u = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (u >= a.n_vec) return;
     u32x4 n[kCountPlanes], z[kCountPlanes];

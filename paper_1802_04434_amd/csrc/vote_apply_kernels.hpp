@@ -187,68 +187,81 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(const ApplyArgs a) {
 
 // ------------------------------------------------ "(good)": vote sums ----
 // Section 4's first scheme sends back the sum of the workers' signs instead of
-// its sign.  A lane owns runs of 16 consecutive coordinates (half a packed
-// word each) so that the 16 int8 sums of a run leave as one 128-bit store and a
-// wave's stores are contiguous; the counts of "-" votes sit in byte lanes of
-// four registers per run.  The words of a batch of workers are loaded before
-// any of them is used.
+// its sign.  Bit-sliced like the vote: a lane loads 128 coordinates (four words)
+// of every worker with one 128-bit load and ripples them into the binary planes
+// of the count of "-" votes; only at the end are the planes turned into one
+// int8 per coordinate.  A lane's 128 sums are contiguous in memory, so the block
+// passes them through LDS and stores them in coordinate order (a wave's store is
+// 1024 contiguous bytes).
 
 struct VoteSumArgs {
     const uint32_t *packed[64];
     int8_t *sums;
     int M;
     size_t d;
-    size_t n_halves;   // ceil(d / 16)
+    size_t n_vec;      // 128-bit groups of packed words, padding included
 };
 
-constexpr int kVoteSumRows = 4;    // half-words per lane (each kBlock half-words apart)
-constexpr int kVoteSumBatch = 8;   // workers whose words are loaded together
+constexpr int kVoteSumBatch = 8;           // workers whose words are loaded together
+constexpr int kVoteSumLaneBytes = 128;     // a lane's 128 coordinates give 128 int8 sums
+constexpr int kVoteSumLdsStride = 144;     // ... kept 144 bytes apart in LDS (spreads the banks)
 
+// P = number of binary planes of the count of "-" votes: counts up to M < 2^P
+template <int P>
 __global__ __launch_bounds__(kBlock) void vote_sum_kernel(const VoteSumArgs a) {
-    constexpr int R = kVoteSumRows;
-    size_t h[R];
-    bool live[R];
-    uint32_t counts[R][4];
+    __shared__ __align__(16) unsigned char tile[kBlock * kVoteSumLdsStride];
+    const int tid = threadIdx.x;
+    const size_t u = (size_t)blockIdx.x * kBlock + tid;
+    const bool live = u < a.n_vec;
+    const u32x4 zero = {0, 0, 0, 0};
+    u32x4 plane[P];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        h[r] = ((size_t)blockIdx.x * R + r) * kBlock + threadIdx.x;
-        live[r] = h[r] < a.n_halves;
-#pragma unroll
-        for (int n = 0; n < 4; ++n) counts[r][n] = 0;
-    }
+    for (int k = 0; k < P; ++k) plane[k] = zero;
+    // count planes: every worker's four words are rippled in with half adders
     for (int w0 = 0; w0 < a.M; w0 += kVoteSumBatch) {
-        uint32_t word[kVoteSumBatch][R];
+        u32x4 in[kVoteSumBatch];
 #pragma unroll
         for (int j = 0; j < kVoteSumBatch; ++j)
-            if (w0 + j < a.M) {
-#pragma unroll
-                for (int r = 0; r < R; ++r) word[j][r] = live[r] ? a.packed[w0 + j][h[r] >> 1] : 0u;   // two lanes share a word
-            }
+            if (w0 + j < a.M) in[j] = live ? ld_stream(reinterpret_cast<const u32x4 *>(a.packed[w0 + j]) + u) : zero;
         __builtin_amdgcn_sched_barrier(0);   // the batch's loads are all in flight before the first is used
 #pragma unroll
         for (int j = 0; j < kVoteSumBatch; ++j)
             if (w0 + j < a.M) {
+                u32x4 carry = in[j];
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const uint32_t bits = (word[j][r] >> ((unsigned)(h[r] & 1) * 16u)) & 0xFFFFu;
-#pragma unroll
-                    for (int n = 0; n < 4; ++n) counts[r][n] += spread_nibble((bits >> (4 * n)) & 0xFu);
+                for (int k = 0; k < P; ++k) {
+                    const u32x4 t = plane[k] & carry;
+                    plane[k] ^= carry;
+                    carry = t;
                 }
             }
     }
+    // planes -> one int8 sum per coordinate: the lane's 128 sums go to LDS as eight 16-byte pieces
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        if (!live[r]) continue;
-        u32x4 out;
-        out.x = sums_word(counts[r][0], a.M);
-        out.y = sums_word(counts[r][1], a.M);
-        out.z = sums_word(counts[r][2], a.M);
-        out.w = sums_word(counts[r][3], a.M);
-        const size_t first = h[r] * 16;
+    for (int q = 0; q < 8; ++q) {
+        u32x4 piece;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int shift = 4 * ((q & 1) * 4 + e);     // nibble of word q / 2
+            uint32_t counts = 0;
+#pragma unroll
+            for (int k = 0; k < P; ++k) counts += spread_nibble((plane[k][q >> 1] >> shift) & 0xFu) << k;
+            piece[e] = sums_word(counts, a.M);
+        }
+        *reinterpret_cast<u32x4 *>(tile + tid * kVoteSumLdsStride + 16 * q) = piece;
+    }
+    __syncthreads();
+    // ... and leave in the order of the coordinates: a wave's store is 1024 contiguous bytes
+    const size_t base = (size_t)blockIdx.x * (kBlock * kVoteSumLaneBytes);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int c = j * kBlock + tid;                  // 16-byte piece within the block's output
+        const u32x4 piece = *reinterpret_cast<const u32x4 *>(tile + (c >> 3) * kVoteSumLdsStride + 16 * (c & 7));
+        const size_t first = base + 16 * (size_t)c;
         if (first + 16 <= a.d) {
-            st_stream(reinterpret_cast<u32x4 *>(a.sums + first), out);
-        } else {
-            const uint32_t words[4] = {out.x, out.y, out.z, out.w};
+            st_stream(reinterpret_cast<u32x4 *>(a.sums + first), piece);
+        } else if (first < a.d) {
+            const uint32_t words[4] = {piece.x, piece.y, piece.z, piece.w};
             for (size_t i = first; i < a.d; ++i)
                 a.sums[i] = (int8_t)(words[(i - first) >> 2] >> (8 * ((i - first) & 3)));
         }
