@@ -280,7 +280,7 @@ int ss_density(const float *v, size_t d, double *out, void *workspace, void *hip
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same kernel, same results bit for bit as ss_density; the
  * partial sums live in a fixed array inside the library instead
- * (ss_density_workspace_bytes() bytes = 16,448, one copy per device, held until
+ * (ss_density_workspace_bytes() bytes = 4,160, one copy per device, held until
  * the process ends).  The call allocates and frees nothing.
  *   v, out  as for ss_density
  *   d       at most SS_DENSITY_STATIC_MAX_D coordinates, else SS_ERR_RANGE

@@ -550,13 +550,13 @@ static int density_impl(const float *v, size_t d, double *out, ss::DensityScratc
     a.out = out;
     a.scratch = scratch;
     a.d = d;
-    a.n_tiles = d / ((size_t)ss::kDensityRows * ss::kRowCoords);
+    a.n_tiles = d / ((size_t)ss::kDensityRows * ss::kDensityThreads * ss::kQuad);
     // every block gets the same number of tiles (the last one possibly fewer): the grid is a
     // function of d alone, which is what fixes the order of the additions
     const size_t per_block = (a.n_tiles + ss::kDensityMaxBlocks - 1) / ss::kDensityMaxBlocks;
     size_t grid = per_block ? (a.n_tiles + per_block - 1) / per_block : 1;
     if (grid == 0) grid = 1;
-    return launch(ss::density_kernel, grid, 0, stream, a);
+    return launch(ss::density_kernel, grid, 0, stream, a, ss::kDensityThreads);
 }
 
 int ss_density(const float *v, size_t d, double *out, void *workspace, void *hip_stream) {

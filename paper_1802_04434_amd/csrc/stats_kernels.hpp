@@ -110,14 +110,18 @@ __global__ __launch_bounds__(kBlock) void welford_sigma_kernel(const SigmaArgs a
 
 // ------------------------------------------------------------- density ----
 // One launch, fixed summation order.  Block b owns tiles b, b + G, b + 2G, ...
-// (G = gridDim.x, a function of d alone); each lane adds its elements in that
+// (G = gridDim.x <= kDensityMaxBlocks, a function of d alone); each lane adds its elements in that
 // order in fp64, lanes combine through a shuffle tree, waves through LDS, and
 // the block's two sums go to slot b of a scratch array.  The block that takes
 // the last ticket adds the G slots in a fixed order (whichever block it is),
 // writes the result and puts the ticket back to zero for the next call.
 
-constexpr int kDensityMaxBlocks = 1024;
-constexpr int kDensityRows = 8;          // rows of kRowCoords coordinates per tile
+// Few, large blocks: the tickets are atomics on one address and cost about 11 ns each, one after
+// the other, at the very end of the launch (measured: 780 blocks of 256 threads 25 us at
+// d = 25.6 M, 223 blocks of 512 threads 18 us; a plain read of the same bytes 16 us).
+constexpr int kDensityMaxBlocks = 256;
+constexpr int kDensityThreads = 512;
+constexpr int kDensityRows = 8;          // rows of kDensityThreads * 4 coordinates per tile
 
 // layout of the scratch area: ticket counter, then one pair of sums per block
 struct DensityScratch {
@@ -141,7 +145,7 @@ __device__ __forceinline__ void accumulate(float v, double &l1, double &l2sq) {
 }
 
 // sum over the block of each lane's (s1, s2), in a fixed order; valid in thread 0
-__device__ __forceinline__ void block_sum(double &s1, double &s2, double (*part)[kBlock / 64]) {
+__device__ __forceinline__ void block_sum(double &s1, double &s2, double (*part)[kDensityThreads / 64]) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         s1 += __shfl_down(s1, off, 64);
@@ -157,7 +161,7 @@ __device__ __forceinline__ void block_sum(double &s1, double &s2, double (*part)
         s1 = part[0][0];
         s2 = part[1][0];
 #pragma unroll
-        for (int w = 1; w < kBlock / 64; ++w) {
+        for (int w = 1; w < kDensityThreads / 64; ++w) {
             s1 += part[0][w];
             s2 += part[1][w];
         }
@@ -165,9 +169,10 @@ __device__ __forceinline__ void block_sum(double &s1, double &s2, double (*part)
     __syncthreads();
 }
 
-__global__ __launch_bounds__(kBlock) void density_kernel(const DensityArgs a) {
+__global__ __launch_bounds__(kDensityThreads) void density_kernel(const DensityArgs a) {
     constexpr int R = kDensityRows;
-    __shared__ double part[2][kBlock / 64];
+    constexpr int B = kDensityThreads;
+    __shared__ double part[2][B / 64];
     __shared__ int is_last;
     const int tid = threadIdx.x;
     const unsigned G = gridDim.x;
@@ -176,18 +181,23 @@ __global__ __launch_bounds__(kBlock) void density_kernel(const DensityArgs a) {
         f32x4 v[R];
 #pragma unroll
         for (int r = 0; r < R; ++r)
-            v[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.v) + (tile * R + r) * kBlock + tid);
+            v[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.v) + (tile * R + r) * B + tid);
+        // a tile's 32 elements first, then the tile into the running sums: the longest chain of
+        // additions is 32 + (tiles per block), not their product
+        double t1 = 0.0, t2 = 0.0;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            accumulate(v[r].x, l1, l2sq);
-            accumulate(v[r].y, l1, l2sq);
-            accumulate(v[r].z, l1, l2sq);
-            accumulate(v[r].w, l1, l2sq);
+            accumulate(v[r].x, t1, t2);
+            accumulate(v[r].y, t1, t2);
+            accumulate(v[r].z, t1, t2);
+            accumulate(v[r].w, t1, t2);
         }
+        l1 += t1;
+        l2sq += t2;
     }
     // what does not fill a tile: spread over the whole grid, one element per thread and turn
-    const size_t done = a.n_tiles * (size_t)(R * kRowCoords);
-    for (size_t i = done + (size_t)blockIdx.x * kBlock + tid; i < a.d; i += (size_t)G * kBlock)
+    const size_t done = a.n_tiles * (size_t)(R * B * kQuad);
+    for (size_t i = done + (size_t)blockIdx.x * B + tid; i < a.d; i += (size_t)G * B)
         accumulate(a.v[i], l1, l2sq);
     block_sum(l1, l2sq, part);
     if (tid == 0) {
@@ -207,7 +217,7 @@ __global__ __launch_bounds__(kBlock) void density_kernel(const DensityArgs a) {
     // every other block's slot was performed before its ticket, and this block's loads below are
     // device-scope loads issued after the last ticket came back
     double s1 = 0.0, s2 = 0.0;
-    for (unsigned b = tid; b < G; b += kBlock) {
+    for (unsigned b = tid; b < G; b += B) {
         s1 += __hip_atomic_load(&a.scratch->partial[b][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s2 += __hip_atomic_load(&a.scratch->partial[b][1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }

@@ -440,6 +440,37 @@ def test_fused_step_large_d_streaming_shape(ss, oracle, M, dtype, momentum):
         assert_same_floats(x_dev, x, "x step %d" % k)
 
 
+@pytest.mark.parametrize("M,dtype,momentum", [(13, "bf16", True), (6, "bf16", True), (33, "f32", True),
+                                              (64, "f32", False), (17, "bf16", False)])
+def test_fused_step_streaming_shape_any_worker_count(ss, oracle, M, dtype, momentum):
+    # worker counts without a kernel of their own (the run-time-M kernel), in every streaming
+    # shape: stages of two workers plus a remainder (bf16 + momentum, odd M), one worker per stage
+    # (fp32 + momentum), several gradient loads per lane (no momentum); ragged d, two steps,
+    # per-worker bits on the second
+    d = (1 << 20) + 4096 + 333
+    rng = np.random.default_rng(1000 + M)
+    m = [make_momentum(rng, d) for _ in range(M)] if momentum else None
+    x = (rng.standard_normal(d) * 0.05).astype(np.float32)
+    m_dev = [torch.from_numpy(a).to(DEV) for a in m] if momentum else None
+    x_dev = torch.from_numpy(x).to(DEV)
+    for k in range(2):
+        g = [make_grad(rng, d, dtype, scale=0.5) for _ in range(M)]
+        g_dev = [t.to(DEV) for t in g]
+        voted = dirty_bits(ss, d)
+        packed = [dirty_bits(ss, d) for _ in range(M)] if k == 1 else None
+        ss.signum_vote_step(g_dev, m_dev, 0.9, 1e-4, x_dev, voted, packed)
+        want_voted, want_bits = oracle.signum_vote_step([synth.as_numpy(t) for t in g], m, 0.9, 1e-4, x,
+                                                        want_packed=True, threads=16)
+        assert np.array_equal(bits_np(voted), want_voted), ("voted", k)
+        if packed is not None:
+            for w in range(M):
+                assert np.array_equal(bits_np(packed[w]), want_bits[w]), ("packed", k, w)
+        if momentum:
+            for w in range(M):
+                assert_same_floats(m_dev[w], m[w], "m[%d] step %d" % (w, k))
+        assert_same_floats(x_dev, x, "x step %d" % k)
+
+
 @pytest.mark.parametrize("M,dtype,flags", [(10, "f32", 0), (12, "f32", 1), (4, "bf16", 0), (5, "bf16", 1)])
 def test_fused_step_with_packed_out_at_many_workers(ss, oracle, M, dtype, flags):
     # d >= 2^24 with per-worker bits requested: the call may hand the signs

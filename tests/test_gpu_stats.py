@@ -14,12 +14,13 @@ pytestmark = pytest.mark.gpu
 
 # Both sums add exact, non-negative fp64 terms, so every rounding error has the
 # same sign bound: relative error <= (number of additions on the longest chain)
-# * 2^-53.  A lane adds at most ceil(d / (8192 * G)) * 32 + d / (256 * G) + 1
-# terms one after the other (G <= 1024 blocks, at least half of that once
-# d >= 2^23), then 6 + 3 additions combine lanes and waves, and the last block
-# adds at most 4 + 6 + 3 more: for d <= 2^31 that is under 2^14 + 64 roundings of
-# 2^-53 each, < 1e-12 - the sizes tested here stay far below it.  The oracle
-# accumulates in 80-bit long double (its own error is 2^-11 of that).
+# * 2^-53.  A lane adds the 32 elements of a tile, then the tile to its running
+# sum: 32 + (tiles per block) + (at most one tail element per 131,072) additions,
+# with at most 256 blocks of 16,384 coordinates per tile; then 6 + 7 additions
+# combine lanes and waves, and the last block adds 1 + 6 + 7 more.  At
+# d = 2^31 that is under 600 roundings of 2^-53 each, < 1e-13; the tolerance
+# leaves a factor of ten.  The oracle accumulates in 80-bit long double (its own
+# error is 2^-11 of that).
 DENSITY_RTOL = 1e-12
 
 
