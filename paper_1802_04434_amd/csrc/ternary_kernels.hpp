@@ -212,39 +212,50 @@ __device__ __forceinline__ u32x4 planes_ge(const u32x4 (&t)[N], int c) {
     return ge;
 }
 
+// NB workers' planes loaded together (no test between the loads), then counted
+template <int P, int NB>
+__device__ __forceinline__ void quorum_batch(const uint32_t *const *neg, const uint32_t *const *zero, size_t u,
+                                             u32x4 (&n)[P], u32x4 (&z)[P]) {
+    u32x4 nw[NB], zw[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        nw[j] = ld_stream(reinterpret_cast<const u32x4 *>(neg[j]) + u);
+        zw[j] = ld_stream(reinterpret_cast<const u32x4 *>(zero[j]) + u);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        u32x4 cz = zw[j];
+        u32x4 cn = nw[j] & ~zw[j];   // an abstention is not a vote, whatever the other plane says
+#pragma unroll
+        for (int k = 0; k < P; ++k) {
+            const u32x4 tn = n[k] & cn, tz = z[k] & cz;
+            n[k] ^= cn;
+            z[k] ^= cz;
+            cn = tn;
+            cz = tz;
+        }
+    }
+}
+
 // P = number of binary planes of n and z (M < 2^P); t = 2 n + z <= 2 M needs one more
 template <int P>
 __global__ __launch_bounds__(kBlock) void quorum_vote_kernel(const QuorumVoteArgs a) {
     constexpr int kCountPlanes = P;
     constexpr int kTotalPlanes = P + 1;
+    static_assert(kQuorumBatch == 4, "the remainder switch below lists 1 .. 3");
     const size_t u = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (u >= a.n_vec) return;
     u32x4 n[kCountPlanes], z[kCountPlanes];
 #pragma unroll
     for (int k = 0; k < kCountPlanes; ++k) n[k] = z[k] = splat(0u);
-    for (int w0 = 0; w0 < a.M; w0 += kQuorumBatch) {
-        u32x4 nw[kQuorumBatch], zw[kQuorumBatch];
-#pragma unroll
-        for (int j = 0; j < kQuorumBatch; ++j)
-            if (w0 + j < a.M) {
-                nw[j] = ld_stream(reinterpret_cast<const u32x4 *>(a.neg[w0 + j]) + u);
-                zw[j] = ld_stream(reinterpret_cast<const u32x4 *>(a.zero[w0 + j]) + u);
-            }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < kQuorumBatch; ++j)
-            if (w0 + j < a.M) {
-                u32x4 cz = zw[j];
-                u32x4 cn = nw[j] & ~zw[j];   // an abstention is not a vote, whatever the other plane says
-#pragma unroll
-                for (int k = 0; k < kCountPlanes; ++k) {
-                    const u32x4 tn = n[k] & cn, tz = z[k] & cz;
-                    n[k] ^= cn;
-                    z[k] ^= cz;
-                    cn = tn;
-                    cz = tz;
-                }
-            }
+    int w0 = 0;
+    for (; w0 + kQuorumBatch <= a.M; w0 += kQuorumBatch) quorum_batch<P, kQuorumBatch>(a.neg + w0, a.zero + w0, u, n, z);
+    switch (a.M - w0) {
+        case 1: quorum_batch<P, 1>(a.neg + w0, a.zero + w0, u, n, z); break;
+        case 2: quorum_batch<P, 2>(a.neg + w0, a.zero + w0, u, n, z); break;
+        case 3: quorum_batch<P, 3>(a.neg + w0, a.zero + w0, u, n, z); break;
+        default: break;
     }
     // t = 2 n + z
     u32x4 t[kTotalPlanes];

@@ -106,6 +106,44 @@ __global__ __launch_bounds__(kBlock) void vote_kernel(const VoteArgs<M> a) {
 // and every word is added with a ripple of half adders.
 constexpr int kPlanes = 7;   // counts up to 64 < 2^7
 
+// NB workers' 128-bit groups loaded together (no test between the loads: all NB are in flight
+// before the first is used), then rippled into the P count planes with half adders
+template <int P, int NB>
+__device__ __forceinline__ void ripple_batch(const uint32_t *const *packed, size_t u, u32x4 (&plane)[P]) {
+    u32x4 in[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) in[j] = ld_stream(reinterpret_cast<const u32x4 *>(packed[j]) + u);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        u32x4 carry = in[j];
+#pragma unroll
+        for (int k = 0; k < P; ++k) {
+            const u32x4 t = plane[k] & carry;
+            plane[k] ^= carry;
+            carry = t;
+        }
+    }
+}
+
+// all M workers: full batches of NB, then the remaining 1 .. NB-1 as one batch of exactly that size
+template <int P, int NB>
+__device__ __forceinline__ void ripple_all(const uint32_t *const *packed, int M, size_t u, u32x4 (&plane)[P]) {
+    static_assert(NB == 8, "the remainder switch below lists 1 .. 7");
+    int w0 = 0;
+    for (; w0 + NB <= M; w0 += NB) ripple_batch<P, NB>(packed + w0, u, plane);
+    switch (M - w0) {
+        case 1: ripple_batch<P, 1>(packed + w0, u, plane); break;
+        case 2: ripple_batch<P, 2>(packed + w0, u, plane); break;
+        case 3: ripple_batch<P, 3>(packed + w0, u, plane); break;
+        case 4: ripple_batch<P, 4>(packed + w0, u, plane); break;
+        case 5: ripple_batch<P, 5>(packed + w0, u, plane); break;
+        case 6: ripple_batch<P, 6>(packed + w0, u, plane); break;
+        case 7: ripple_batch<P, 7>(packed + w0, u, plane); break;
+        default: break;
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void vote_kernel_any(const VoteArgs<64> a) {
     const size_t u = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (u >= a.n_vec) return;
@@ -113,25 +151,7 @@ __global__ __launch_bounds__(kBlock) void vote_kernel_any(const VoteArgs<64> a) 
     u32x4 plane[kPlanes];
 #pragma unroll
     for (int k = 0; k < kPlanes; ++k) plane[k] = u32x4{0, 0, 0, 0};
-    constexpr int kBatch = 8;
-    for (int w0 = 0; w0 < a.M; w0 += kBatch) {
-        u32x4 in[kBatch];
-#pragma unroll
-        for (int j = 0; j < kBatch; ++j)
-            if (w0 + j < a.M) in[j] = ld_stream(reinterpret_cast<const u32x4 *>(a.packed[w0 + j]) + u);
-#pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-            if (w0 + j < a.M) {
-                u32x4 carry = in[j];
-#pragma unroll
-                for (int k = 0; k < kPlanes; ++k) {
-                    const u32x4 t = plane[k] & carry;
-                    plane[k] ^= carry;
-                    carry = t;
-                }
-            }
-        }
-    }
+    ripple_all<kPlanes, 8>(a.packed, a.M, u, plane);
     u32x4 ge = u32x4{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
 #pragma unroll
     for (int k = 0; k < kPlanes; ++k) ge = ((T >> k) & 1) ? (plane[k] & ge) : (plane[k] | ge);
@@ -212,30 +232,13 @@ __global__ __launch_bounds__(kBlock) void vote_sum_kernel(const VoteSumArgs a) {
     __shared__ __align__(16) unsigned char tile[kBlock * kVoteSumLdsStride];
     const int tid = threadIdx.x;
     const size_t u = (size_t)blockIdx.x * kBlock + tid;
-    const bool live = u < a.n_vec;
-    const u32x4 zero = {0, 0, 0, 0};
+    // lanes beyond the last group (last block only) re-read the last group: their coordinates
+    // lie at or beyond d and are never stored
+    const size_t ul = u < a.n_vec ? u : a.n_vec - 1;
     u32x4 plane[P];
 #pragma unroll
-    for (int k = 0; k < P; ++k) plane[k] = zero;
-    // count planes: every worker's four words are rippled in with half adders
-    for (int w0 = 0; w0 < a.M; w0 += kVoteSumBatch) {
-        u32x4 in[kVoteSumBatch];
-#pragma unroll
-        for (int j = 0; j < kVoteSumBatch; ++j)
-            if (w0 + j < a.M) in[j] = live ? ld_stream(reinterpret_cast<const u32x4 *>(a.packed[w0 + j]) + u) : zero;
-        __builtin_amdgcn_sched_barrier(0);   // the batch's loads are all in flight before the first is used
-#pragma unroll
-        for (int j = 0; j < kVoteSumBatch; ++j)
-            if (w0 + j < a.M) {
-                u32x4 carry = in[j];
-#pragma unroll
-                for (int k = 0; k < P; ++k) {
-                    const u32x4 t = plane[k] & carry;
-                    plane[k] ^= carry;
-                    carry = t;
-                }
-            }
-    }
+    for (int k = 0; k < P; ++k) plane[k] = u32x4{0, 0, 0, 0};
+    ripple_all<P, kVoteSumBatch>(a.packed, a.M, ul, plane);
     // planes -> one int8 sum per coordinate: the lane's 128 sums go to LDS as eight 16-byte pieces
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
@@ -253,9 +256,21 @@ __global__ __launch_bounds__(kBlock) void vote_sum_kernel(const VoteSumArgs a) {
     __syncthreads();
     // ... and leave in the order of the coordinates: a wave's store is 1024 contiguous bytes
     const size_t base = (size_t)blockIdx.x * (kBlock * kVoteSumLaneBytes);
+    if (base + (size_t)kBlock * kVoteSumLaneBytes <= a.d) {      // every block but the last: no test per store
+        u32x4 piece[8];
 #pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int c = j * kBlock + tid;              // 16-byte piece within the block's output
+            piece[j] = *reinterpret_cast<const u32x4 *>(tile + (c >> 3) * kVoteSumLdsStride + 16 * (c & 7));
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            st_stream(reinterpret_cast<u32x4 *>(a.sums + base + 16 * (size_t)(j * kBlock + tid)), piece[j]);
+        return;
+    }
+#pragma unroll 1
     for (int j = 0; j < 8; ++j) {
-        const int c = j * kBlock + tid;                  // 16-byte piece within the block's output
+        const int c = j * kBlock + tid;
         const u32x4 piece = *reinterpret_cast<const u32x4 *>(tile + (c >> 3) * kVoteSumLdsStride + 16 * (c & 7));
         const size_t first = base + 16 * (size_t)c;
         if (first + 16 <= a.d) {
