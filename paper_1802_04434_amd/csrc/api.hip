@@ -245,23 +245,27 @@ int launch_vote_any(const uint32_t *const *packed, int M, uint32_t *voted, size_
 }
 
 // launch helpers of the ternary (vote with abstention) kernels
-template <int BLOCK, int R, int HOLD_KB, bool LOADS_FIRST, bool HAS_M, bool VOTE, typename G>
+template <int BLOCK, int BW, int R, int HOLD_KB, bool LOADS_FIRST, bool HAS_M, bool VOTE, typename G>
 int launch_ternary_shape(ss::TernaryStepArgs &a, size_t d, hipStream_t stream) {
     const Tiling t = make_tiling(d, R, true, BLOCK);
     a.n_tiles = t.n_tiles;
     a.words_total = t.words_total;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    return launch(ss::ternary_step_kernel<BLOCK, R, HOLD_KB, LOADS_FIRST, HAS_M, VOTE, G>, grid, 0, stream, a, BLOCK);
+    return launch(ss::ternary_step_kernel<BLOCK, BW, R, HOLD_KB, LOADS_FIRST, HAS_M, VOTE, G>, grid, 0, stream, a, BLOCK);
 }
 
 template <bool HAS_M, bool VOTE, typename G>
 int launch_ternary(ss::TernaryStepArgs &a, size_t d, hipStream_t stream) {
-    // several workers over a large vector: two blocks per unit, one worker at a time (the
-    // one-block-per-unit shape of the binary step measured 7 % slower here)
-    if (VOTE && a.M >= 2 && d >= kStreamingMinD && lds_per_unit_kb() == kLdsPerUnitKB)
-        return launch_ternary_shape<256, 2, 64, false, HAS_M, VOTE, G>(a, d, stream);
-    return launch_ternary_shape<256, 2, 0, false, HAS_M, VOTE, G>(a, d, stream);
+    constexpr bool kBf16 = std::is_same<G, ss::Bf16Grad>::value;
+    if (VOTE && a.M >= 2 && d >= kStreamingMinD && lds_per_unit_kb() == kLdsPerUnitKB) {
+        // bf16 gradients with momentum, from four workers on: the binary step's shape for that case
+        if (kBf16 && HAS_M && a.M >= 4) return launch_ternary_shape<128, 2, 1, 40, true, HAS_M, VOTE, G>(a, d, stream);
+        // otherwise two blocks per unit, one worker at a time (the one-block-per-unit shape of
+        // the binary step measured 7 % slower here)
+        return launch_ternary_shape<256, 1, 2, 64, false, HAS_M, VOTE, G>(a, d, stream);
+    }
+    return launch_ternary_shape<256, 1, 2, 0, false, HAS_M, VOTE, G>(a, d, stream);
 }
 
 template <bool VOTE>
@@ -544,11 +548,12 @@ int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d, void *
 
 size_t ss_density_workspace_bytes(void) { return sizeof(ss::DensityScratch); }
 
-static int density_impl(const float *v, size_t d, double *out, ss::DensityScratch *scratch, hipStream_t stream) {
+// `partials` is a device address: the caller's workspace, or the looked-up address of the array above
+static int density_impl(const float *v, size_t d, double *out, ss::DensityScratch *partials, hipStream_t stream) {
     ss::DensityArgs a;
     a.v = v;
     a.out = out;
-    a.scratch = scratch;
+    a.scratch = partials;
     a.d = d;
     a.n_tiles = d / ((size_t)ss::kDensityRows * ss::kDensityThreads * ss::kQuad);
     // every block gets the same number of tiles (the last one possibly fewer): the grid is a

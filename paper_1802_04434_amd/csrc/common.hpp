@@ -6,7 +6,8 @@
 //             one 128-bit access per fp32 buffer, one 64-bit access for bf16
 //   8 lanes   own 32 consecutive coordinates = one packed word
 //   wave      64 lanes = 256 coordinates = 8 packed words
-//   block     256 threads = 1024 coordinates per row
+//   block     B threads = 4 B coordinates per row, R rows per block (B = 256 = kBlock
+//             everywhere but in the step kernel's streaming shapes, which use 128-512)
 // The coordinates that do not fill a whole tile go through a scalar path in
 // extra blocks at the end of the same grid (one coordinate per lane; there a
 // wave ballot is already in packed-word order).
@@ -22,7 +23,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kBlock = 256;          // threads per block
+constexpr int kBlock = 256;          // threads per block unless a kernel is launched with its own
 constexpr int kQuad = 4;             // coordinates per lane per row
 constexpr int kRowCoords = kBlock * kQuad;   // 1024
 

@@ -7,22 +7,24 @@
 // element is read once and written once (arxiv 1802.04434).
 //
 // The path is bound by HBM traffic (12 bytes per worker and coordinate plus
-// 8 for x, against a handful of ALU operations).  Two things decide how close
-// to the DRAM's rate it runs, both measured on MI355X:
+// 8 for x, against a handful of ALU operations).  What decides how close to
+// the DRAM's rate it runs, all measured on MI355X:
 //
-//  * Loads of a batch of BW workers are issued into registers before the first
-//    dependent operation or store: a store to one worker's momentum could alias
-//    (as far as the compiler knows) the next worker's loads and would otherwise
-//    serialise them.
-//  * The amount of traffic in flight.  About 32 KB of outstanding loads per
-//    compute unit (8 MB over the chip, the bandwidth-delay product) saturates
-//    HBM; more than that only lengthens the memory system's queues and mixes
-//    more DRAM rows into them, and the rate drops by 5-10 % - the more streams
-//    (workers) the worse.  For large d the kernel therefore walks the workers
-//    ONE AT A TIME (BW = 1, a block touches two input streams and one output
-//    stream at any moment) and the launch caps the resident blocks per compute
-//    unit by asking for dynamic LDS that the kernel never touches (64 KB per
-//    block: two 256-thread blocks fit in a unit's 160 KB).
+//  * The loads of a stage (BW workers x R rows, gradient and momentum) are
+//    issued into registers before the first dependent operation or store: a
+//    store to one worker's momentum could alias (as far as the compiler knows)
+//    the next worker's loads and would otherwise serialise them.
+//  * The amount of traffic in flight.  16-24 KB of outstanding loads per compute
+//    unit (4-6 MB over the chip, the bandwidth-delay product) saturate HBM; more
+//    only lengthens the memory system's queues and mixes more DRAM rows into
+//    them, and the rate drops by 3-10 % - the more streams (workers) the worse.
+//    For large d the kernel therefore takes one or two workers per stage and
+//    the block reserves LDS that it never uses (HOLD_KB), which caps the blocks
+//    that share a compute unit: e.g. 96 KB leaves room for one 512-thread block
+//    in a unit's 160 KB, 64 KB for two 256-thread blocks, 40 KB for four of 128.
+//    The host picks the shape (launch_step_m in api.hip).
+//  * A tile costs (number of stages) x (one memory latency); the x load goes out
+//    with the first stage's loads and the x store overlaps the next tile.
 //    Small d is latency bound instead: there all M workers' loads go out
 //    together (BW = M) and nothing is held back.
 #pragma once

@@ -45,9 +45,61 @@ __device__ __forceinline__ float step_ternary(float x, float delta, uint32_t ans
     return (answer & 2u) ? x : ((answer & 1u) ? x + delta : x - delta);
 }
 
-// BLOCK threads per block, R rows per block, HOLD_KB of LDS reserved to cap the blocks per
-// compute unit, LOADS_FIRST as in the binary step kernel
-template <int BLOCK, int R, int HOLD_KB, bool LOADS_FIRST, bool HAS_M, bool VOTE, typename G>
+// One stage of the vector path: NW consecutive workers starting at w0, R rows (as step_stage
+// of the binary kernel: with LOADS_FIRST every load of the stage is out before the first wait)
+template <int NW, int R, bool LOADS_FIRST, bool HAS_M, bool VOTE, typename G>
+__device__ __forceinline__ void ternary_stage(const TernaryStepArgs &a, int w0, const size_t (&q)[R],
+                                              uint32_t (&n_neg)[R], uint32_t (&n_zero)[R], int lane) {
+    f32x4 gv[R][NW], mv[R][NW];
+#pragma unroll
+    for (int j = 0; j < NW; ++j) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            gv[r][j] = G::load4(a.g[w0 + j], q[r]);
+            if (HAS_M) mv[r][j] = ld_stream(reinterpret_cast<const f32x4 *>(a.m[w0 + j]) + q[r]);
+        }
+    }
+    if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NW; ++j) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            f32x4 v = gv[r][j];
+            if (HAS_M) {
+                const f32x4 m0 = mv[r][j];
+                v.x = momentum(a.beta, a.omb, m0.x, v.x);
+                v.y = momentum(a.beta, a.omb, m0.y, v.y);
+                v.z = momentum(a.beta, a.omb, m0.z, v.z);
+                v.w = momentum(a.beta, a.omb, m0.w, v.w);
+                st_stream(reinterpret_cast<f32x4 *>(a.m[w0 + j]) + q[r], v);
+            }
+            uint32_t zero_nib = 0, neg_nib = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool abstain = __builtin_fabsf(v[c]) < a.tau;
+                zero_nib |= (abstain ? 1u : 0u) << c;
+                neg_nib |= ((!abstain && v[c] < 0.0f) ? 1u : 0u) << c;
+            }
+            if (VOTE) {
+                n_neg[r] += spread_nibble(neg_nib);
+                n_zero[r] += spread_nibble(zero_nib);
+            } else {
+                const uint32_t nw = combine8(neg_nib, lane);
+                const uint32_t zw = combine8(zero_nib, lane);
+                if ((lane & 7) == 0) {
+                    a.neg_out[q[r] >> 3] = nw;
+                    a.zero_out[q[r] >> 3] = zw;
+                }
+            }
+        }
+    }
+    if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
+}
+
+// BLOCK threads per block, BW workers per stage (what M leaves over goes one at a time), R rows
+// per block, HOLD_KB of LDS reserved to cap the blocks per compute unit, LOADS_FIRST as in the
+// binary step kernel
+template <int BLOCK, int BW, int R, int HOLD_KB, bool LOADS_FIRST, bool HAS_M, bool VOTE, typename G>
 __global__ __launch_bounds__(BLOCK) void ternary_step_kernel(const TernaryStepArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -73,45 +125,11 @@ __global__ __launch_bounds__(BLOCK) void ternary_step_kernel(const TernaryStepAr
             n_zero[r] = 0;
             if (VOTE) xv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.x) + q[r]);
         }
-        for (int w = 0; w < M; ++w) {
-            f32x4 gv[R], mv[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                gv[r] = G::load4(a.g[w], q[r]);
-                if (HAS_M) mv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.m[w]) + q[r]);
-            }
-            // every load of this worker is in flight before the first result is waited for
-            if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                f32x4 v = gv[r];
-                if (HAS_M) {
-                    v.x = momentum(a.beta, a.omb, mv[r].x, v.x);
-                    v.y = momentum(a.beta, a.omb, mv[r].y, v.y);
-                    v.z = momentum(a.beta, a.omb, mv[r].z, v.z);
-                    v.w = momentum(a.beta, a.omb, mv[r].w, v.w);
-                    st_stream(reinterpret_cast<f32x4 *>(a.m[w]) + q[r], v);
-                }
-                uint32_t zero_nib = 0, neg_nib = 0;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const bool abstain = __builtin_fabsf(v[c]) < a.tau;
-                    zero_nib |= (abstain ? 1u : 0u) << c;
-                    neg_nib |= ((!abstain && v[c] < 0.0f) ? 1u : 0u) << c;
-                }
-                if (VOTE) {
-                    n_neg[r] += spread_nibble(neg_nib);
-                    n_zero[r] += spread_nibble(zero_nib);
-                } else {
-                    const uint32_t nw = combine8(neg_nib, lane);
-                    const uint32_t zw = combine8(zero_nib, lane);
-                    if ((lane & 7) == 0) {
-                        a.neg_out[q[r] >> 3] = nw;
-                        a.zero_out[q[r] >> 3] = zw;
-                    }
-                }
-            }
+        int w0 = 0;
+        if constexpr (BW > 1) {
+            for (; w0 + BW <= M; w0 += BW) ternary_stage<BW, R, LOADS_FIRST, HAS_M, VOTE, G>(a, w0, q, n_neg, n_zero, lane);
         }
+        for (; w0 < M; ++w0) ternary_stage<1, R, LOADS_FIRST, HAS_M, VOTE, G>(a, w0, q, n_neg, n_zero, lane);
         if (VOTE) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {

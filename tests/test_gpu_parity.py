@@ -128,6 +128,29 @@ def test_majority_vote_exhaustive_patterns(ss, oracle):
         assert np.array_equal(got == -1, 2 * pop > M)
 
 
+def test_majority_vote_over_coordinate_shards(ss, oracle):
+    # How the vote splits over several devices (Algorithm 3 with the server's work divided by
+    # coordinate): shard j holds words [j W/M, (j+1) W/M) of all M workers' vectors and votes
+    # on them alone.  The vote is pointwise, so the shards' results side by side are the vote
+    # over the whole vector.  Shard boundaries are multiples of 128 coordinates (16 bytes).
+    M, d = 8, 3_194_629            # one device's share of the headline workload with 8 workers, ragged end
+    rng = np.random.default_rng(818)
+    n = ss.packed_bytes(d) // 4
+    words = [rng.integers(0, 1 << 32, n, dtype=np.uint64).astype(np.uint32) for _ in range(M)]
+    dev = [torch.from_numpy(w.view(np.int32)).to(DEV) for w in words]
+    whole = dirty_bits(ss, d)
+    ss.majority_vote(dev, whole, d)
+    want = oracle.majority_vote(words, d)
+    assert np.array_equal(bits_np(whole), want)
+    sharded = dirty_bits(ss, d)
+    per = (d // M) // 128 * 128
+    for j in range(M):
+        lo = j * per
+        dj = per if j < M - 1 else d - lo
+        ss.majority_vote([t[lo // 32:] for t in dev], sharded[lo // 32:], dj)
+    assert np.array_equal(bits_np(sharded), want)
+
+
 # ----------------------------------------------------------- apply ------
 
 @pytest.mark.parametrize("d", RAGGED)
