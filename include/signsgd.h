@@ -38,7 +38,8 @@
  *             (g[], m[], packed[]) are HOST arrays of M device pointers; they
  *             are copied into the kernel arguments during the call and may be
  *             freed on return.  The library allocates nothing and keeps no
- *             state between calls.
+ *             state between calls (one exception, stated there: the fixed
+ *             scratch array of ss_density_static).
  * STREAMS     hip_stream is a hipStream_t passed as void* (NULL: the default
  *             stream).  Work is enqueued and the call returns without
  *             synchronising.  Calls are thread safe.
