@@ -113,6 +113,26 @@ constexpr int kLdsPerUnitKB = 160;   // what the reservations below assume; chec
 constexpr size_t kSplitMinD = (size_t)1 << 24;
 constexpr int kSplitMinWorkers = 10;
 
+// LDS of one compute unit of the current device, in KB; 0 if the runtime will not say.  A pure
+// query: nothing is remembered between calls.
+inline int lds_per_unit_kb() {
+    int dev = 0, bytes = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess) return 0;
+    return bytes / 1024;
+}
+
+// The kernels that stream one or a few buffers (pack, apply, copy, Welford, the stand-alone votes)
+// are launched with as many blocks per unit as fit while the buffers are small; from about a
+// gigabyte per array on every one of them runs 3-12 % faster with roughly 24 KB of loads in flight
+// per compute unit (six 256-thread blocks of one row, or four of two rows), which an LDS
+// reservation enforces.  Measured on MI355X for 2^27 .. 1.5 * 2^30 coordinates; each entry point
+// states the shape it takes on either side of its threshold.
+constexpr size_t kLargeD = (size_t)1 << 28;
+
+// the reservations are sized for a unit with kLdsPerUnitKB of LDS: on anything else, no cap
+inline bool caps_apply() { return lds_per_unit_kb() == kLdsPerUnitKB; }
+
 constexpr int latency_rows(int m, bool has_m) {
     const int streams = m * (has_m ? 2 : 1);
     return streams >= 8 ? 1 : streams >= 4 ? 2 : 4;
@@ -150,15 +170,6 @@ int launch_step_shape(ss::StepArgs<NPTR> &a, size_t d, hipStream_t stream) {
     return launch(ss::step_kernel<MT, NPTR, BLOCK, BW, R, HOLD_KB, LOADS_FIRST, HAS_M, VOTE, G>, grid, 0, stream, a, BLOCK);
 }
 
-// LDS of one compute unit of the current device, in KB; 0 if the runtime will not say.  A pure
-// query: nothing is remembered between calls.
-inline int lds_per_unit_kb() {
-    int dev = 0, bytes = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess) return 0;
-    return bytes / 1024;
-}
-
 // what distinguishes the variants of the step (see ss_step_flags)
 struct StepVariant {
     unsigned flags;
@@ -178,6 +189,10 @@ int launch_step_m(int M, const void *const *g, float *const *m, uint32_t *const 
     constexpr bool kBf16 = std::is_same<G, ss::Bf16Grad>::value;
     if constexpr (MT == 1) {
         // a single worker is two or three streams whatever the shape: no cap needed
+        if constexpr (!VOTE && HAS_M) {
+            // pack over a large vector: one row per block, six blocks per unit
+            if (d >= kLargeD && caps_apply()) return launch_step_shape<1, NPTR, 256, 1, 1, 24, true, true, false, G>(a, d, stream);
+        }
         constexpr int R = VOTE ? 2 : 4;
         return launch_step_shape<1, NPTR, 256, 1, R, 0, false, HAS_M, VOTE, G>(a, d, stream);
     } else {
@@ -219,6 +234,11 @@ int launch_step(int M, const void *const *g, float *const *m, uint32_t *const *p
 #undef SS_CASE
 }
 
+// the votes read M buffers at once; with packed buffers beyond ~128 MB each (d >= 2^30) two blocks
+// per unit are faster than eight (+12 % at d = 1.5 G, M = 8), below that nothing is gained
+constexpr size_t kVoteCapMinD = (size_t)1 << 30;
+constexpr int kVoteHoldKB = 64;
+
 template <int M>
 int launch_vote_fixed(const uint32_t *const *packed, uint32_t *voted, size_t d, hipStream_t stream) {
     ss::VoteArgs<M> a;
@@ -229,7 +249,8 @@ int launch_vote_fixed(const uint32_t *const *packed, uint32_t *voted, size_t d, 
     a.n_vec = ss_packed_bytes(d) / 16;
     const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    return launch(ss::vote_kernel<M>, grid, 0, stream, a);
+    if (d >= kVoteCapMinD && caps_apply()) return launch(ss::vote_kernel<M, kVoteHoldKB>, grid, 0, stream, a);
+    return launch(ss::vote_kernel<M, 0>, grid, 0, stream, a);
 }
 
 int launch_vote_any(const uint32_t *const *packed, int M, uint32_t *voted, size_t d, hipStream_t stream) {
@@ -241,7 +262,8 @@ int launch_vote_any(const uint32_t *const *packed, int M, uint32_t *voted, size_
     a.n_vec = ss_packed_bytes(d) / 16;
     const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    return launch(ss::vote_kernel_any, grid, 0, stream, a);
+    if (d >= kVoteCapMinD && caps_apply()) return launch(ss::vote_kernel_any<kVoteHoldKB>, grid, 0, stream, a);
+    return launch(ss::vote_kernel_any<0>, grid, 0, stream, a);
 }
 
 // launch helpers of the ternary (vote with abstention) kernels
@@ -264,6 +286,13 @@ int launch_ternary(ss::TernaryStepArgs &a, size_t d, hipStream_t stream) {
         // otherwise two blocks per unit, one worker at a time (the one-block-per-unit shape of
         // the binary step measured 7 % slower here)
         return launch_ternary_shape<256, 1, 2, 64, false, HAS_M, VOTE, G>(a, d, stream);
+    }
+    if constexpr (!VOTE && HAS_M) {
+        // one worker's ternary pack: four blocks of two rows per unit, six of one row over a large vector
+        if (caps_apply()) {
+            if (d >= kLargeD) return launch_ternary_shape<256, 1, 1, 24, true, true, false, G>(a, d, stream);
+            if (d >= kStreamingMinD) return launch_ternary_shape<256, 1, 2, 40, true, true, false, G>(a, d, stream);
+        }
     }
     return launch_ternary_shape<256, 1, 2, 0, false, HAS_M, VOTE, G>(a, d, stream);
 }
@@ -368,8 +397,8 @@ int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d, void *h
     if (!aligned16(x) || !aligned16(bits)) return SS_ERR_ALIGN;
     Span spans[2] = {span(x, d * sizeof(float), true), span(bits, ss_packed_words(d) * 4, false)};
     if (written_spans_overlap(spans, 2)) return SS_ERR_ARG;
-    constexpr int R = 4;
-    const Tiling t = make_tiling(d, R, false);
+    const bool large = d >= kLargeD && caps_apply();   // then one row per block, six blocks per unit
+    const Tiling t = make_tiling(d, large ? 1 : 4, false);
     ss::ApplyArgs a;
     a.x = x;
     a.bits = bits;
@@ -378,7 +407,9 @@ int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d, void *h
     a.n_tiles = t.n_tiles;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    return launch(ss::apply_kernel<R>, grid, 0, static_cast<hipStream_t>(hip_stream), a);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (large) return launch(ss::apply_kernel<1, 24, true>, grid, 0, stream, a);
+    return launch(ss::apply_kernel<4, 0, false>, grid, 0, stream, a);
 }
 
 int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m, int M, float beta, float delta,
@@ -471,14 +502,25 @@ int ss_vote_sum(const uint32_t *const *packed, int M, int8_t *sums, size_t d, vo
     const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
     if (grid > kMaxGrid) return SS_ERR_ARG;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // beyond cache-resident sizes two blocks per unit instead of four (the tile in LDS already
+    // limits them to four): +3 % at d = 138 M, +9 % at 1.5 G
+    constexpr int kVoteSumHoldKB = 24;
+    const bool capped = d >= ((size_t)1 << 27) && caps_apply();
     switch (count_planes(M)) {
-        case 1: return launch(ss::vote_sum_kernel<1>, grid, 0, stream, a);
-        case 2: return launch(ss::vote_sum_kernel<2>, grid, 0, stream, a);
-        case 3: return launch(ss::vote_sum_kernel<3>, grid, 0, stream, a);
-        case 4: return launch(ss::vote_sum_kernel<4>, grid, 0, stream, a);
-        case 5: return launch(ss::vote_sum_kernel<5>, grid, 0, stream, a);
-        case 6: return launch(ss::vote_sum_kernel<6>, grid, 0, stream, a);
-        default: return launch(ss::vote_sum_kernel<7>, grid, 0, stream, a);
+        case 1: return capped ? launch(ss::vote_sum_kernel<1, kVoteSumHoldKB>, grid, 0, stream, a)
+                              : launch(ss::vote_sum_kernel<1, 0>, grid, 0, stream, a);
+        case 2: return capped ? launch(ss::vote_sum_kernel<2, kVoteSumHoldKB>, grid, 0, stream, a)
+                              : launch(ss::vote_sum_kernel<2, 0>, grid, 0, stream, a);
+        case 3: return capped ? launch(ss::vote_sum_kernel<3, kVoteSumHoldKB>, grid, 0, stream, a)
+                              : launch(ss::vote_sum_kernel<3, 0>, grid, 0, stream, a);
+        case 4: return capped ? launch(ss::vote_sum_kernel<4, kVoteSumHoldKB>, grid, 0, stream, a)
+                              : launch(ss::vote_sum_kernel<4, 0>, grid, 0, stream, a);
+        case 5: return capped ? launch(ss::vote_sum_kernel<5, kVoteSumHoldKB>, grid, 0, stream, a)
+                              : launch(ss::vote_sum_kernel<5, 0>, grid, 0, stream, a);
+        case 6: return capped ? launch(ss::vote_sum_kernel<6, kVoteSumHoldKB>, grid, 0, stream, a)
+                              : launch(ss::vote_sum_kernel<6, 0>, grid, 0, stream, a);
+        default: return capped ? launch(ss::vote_sum_kernel<7, kVoteSumHoldKB>, grid, 0, stream, a)
+                               : launch(ss::vote_sum_kernel<7, 0>, grid, 0, stream, a);
     }
 }
 
@@ -488,8 +530,8 @@ int ss_sum_apply(float *x, const int8_t *sums, float delta, size_t d, void *hip_
     if (!aligned16(x) || !aligned16(sums)) return SS_ERR_ALIGN;
     Span spans[2] = {span(x, d * sizeof(float), true), span(sums, d, false)};
     if (written_spans_overlap(spans, 2)) return SS_ERR_ARG;
-    constexpr int R = 4;
-    const Tiling t = make_tiling(d, R, false);
+    const bool large = d >= kLargeD && caps_apply();   // then one row per block, six blocks per unit
+    const Tiling t = make_tiling(d, large ? 1 : 4, false);
     ss::SumApplyArgs a;
     a.x = x;
     a.sums = sums;
@@ -498,7 +540,9 @@ int ss_sum_apply(float *x, const int8_t *sums, float delta, size_t d, void *hip_
     a.n_tiles = t.n_tiles;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    return launch(ss::sum_apply_kernel<R>, grid, 0, static_cast<hipStream_t>(hip_stream), a);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (large) return launch(ss::sum_apply_kernel<1, 24, true>, grid, 0, stream, a);
+    return launch(ss::sum_apply_kernel<4, 0, false>, grid, 0, stream, a);
 }
 
 int ss_welford_update(const void *g, ss_dtype gdt, float *mean, float *m2, uint64_t n, size_t d, void *hip_stream) {
@@ -510,8 +554,10 @@ int ss_welford_update(const void *g, ss_dtype gdt, float *mean, float *m2, uint6
     Span spans[3] = {span(g, d * grad_bytes(gdt), false), span(mean, d * sizeof(float), true),
                      span(m2, d * sizeof(float), true)};
     if (written_spans_overlap(spans, 3)) return SS_ERR_ARG;
-    constexpr int R = 2;
-    const Tiling t = make_tiling(d, R, false);
+    // five streams: from 2^27 coordinates on one row per block and six blocks per unit (+4 % at
+    // d = 138 M, +10 % at 1.5 G), below that two rows and no cap
+    const bool large = d >= ((size_t)1 << 27) && caps_apply();
+    const Tiling t = make_tiling(d, large ? 1 : 2, false);
     ss::WelfordArgs a;
     a.g = g;
     a.mean = mean;
@@ -522,8 +568,12 @@ int ss_welford_update(const void *g, ss_dtype gdt, float *mean, float *m2, uint6
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (gdt == SS_F32) return launch(ss::welford_update_kernel<R, ss::F32Grad>, grid, 0, stream, a);
-    return launch(ss::welford_update_kernel<R, ss::Bf16Grad>, grid, 0, stream, a);
+    if (large) {
+        if (gdt == SS_F32) return launch(ss::welford_update_kernel<1, 24, true, ss::F32Grad>, grid, 0, stream, a);
+        return launch(ss::welford_update_kernel<1, 24, true, ss::Bf16Grad>, grid, 0, stream, a);
+    }
+    if (gdt == SS_F32) return launch(ss::welford_update_kernel<2, 0, false, ss::F32Grad>, grid, 0, stream, a);
+    return launch(ss::welford_update_kernel<2, 0, false, ss::Bf16Grad>, grid, 0, stream, a);
 }
 
 int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d, void *hip_stream) {
@@ -533,8 +583,9 @@ int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d, void *
     if (!aligned16(m2) || !aligned16(sigma)) return SS_ERR_ALIGN;
     Span spans[2] = {span(m2, d * sizeof(float), false), span(sigma, d * sizeof(float), true)};
     if (written_spans_overlap(spans, 2)) return SS_ERR_ARG;
-    constexpr int R = 4;
-    const Tiling t = make_tiling(d, R, false);
+    // two rows per block, six blocks per unit at every size (+2-9 % over four rows and no cap)
+    const bool capped = caps_apply();
+    const Tiling t = make_tiling(d, capped ? 2 : 4, false);
     ss::SigmaArgs a;
     a.m2 = m2;
     a.sigma = sigma;
@@ -543,7 +594,9 @@ int ss_welford_sigma(const float *m2, uint64_t n, float *sigma, size_t d, void *
     a.n_tiles = t.n_tiles;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    return launch(ss::welford_sigma_kernel<R>, grid, 0, static_cast<hipStream_t>(hip_stream), a);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (capped) return launch(ss::welford_sigma_kernel<2, 24, true>, grid, 0, stream, a);
+    return launch(ss::welford_sigma_kernel<4, 0, false>, grid, 0, stream, a);
 }
 
 size_t ss_density_workspace_bytes(void) { return sizeof(ss::DensityScratch); }
@@ -665,14 +718,23 @@ int ss_quorum_vote(const uint32_t *const *neg, const uint32_t *const *zero, int 
     const size_t grid = (a.n_vec + ss::kBlock - 1) / ss::kBlock;
     if (grid > kMaxGrid) return SS_ERR_ARG;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // beyond cache-resident sizes two blocks per unit instead of eight: +2-4 % at d = 138 M, +9 % at 1.5 G
+    const bool capped = d >= ((size_t)1 << 27) && caps_apply();
     switch (count_planes(M)) {
-        case 1: return launch(ss::quorum_vote_kernel<1>, grid, 0, stream, a);
-        case 2: return launch(ss::quorum_vote_kernel<2>, grid, 0, stream, a);
-        case 3: return launch(ss::quorum_vote_kernel<3>, grid, 0, stream, a);
-        case 4: return launch(ss::quorum_vote_kernel<4>, grid, 0, stream, a);
-        case 5: return launch(ss::quorum_vote_kernel<5>, grid, 0, stream, a);
-        case 6: return launch(ss::quorum_vote_kernel<6>, grid, 0, stream, a);
-        default: return launch(ss::quorum_vote_kernel<7>, grid, 0, stream, a);
+        case 1: return capped ? launch(ss::quorum_vote_kernel<1, kVoteHoldKB>, grid, 0, stream, a)
+                              : launch(ss::quorum_vote_kernel<1, 0>, grid, 0, stream, a);
+        case 2: return capped ? launch(ss::quorum_vote_kernel<2, kVoteHoldKB>, grid, 0, stream, a)
+                              : launch(ss::quorum_vote_kernel<2, 0>, grid, 0, stream, a);
+        case 3: return capped ? launch(ss::quorum_vote_kernel<3, kVoteHoldKB>, grid, 0, stream, a)
+                              : launch(ss::quorum_vote_kernel<3, 0>, grid, 0, stream, a);
+        case 4: return capped ? launch(ss::quorum_vote_kernel<4, kVoteHoldKB>, grid, 0, stream, a)
+                              : launch(ss::quorum_vote_kernel<4, 0>, grid, 0, stream, a);
+        case 5: return capped ? launch(ss::quorum_vote_kernel<5, kVoteHoldKB>, grid, 0, stream, a)
+                              : launch(ss::quorum_vote_kernel<5, 0>, grid, 0, stream, a);
+        case 6: return capped ? launch(ss::quorum_vote_kernel<6, kVoteHoldKB>, grid, 0, stream, a)
+                              : launch(ss::quorum_vote_kernel<6, 0>, grid, 0, stream, a);
+        default: return capped ? launch(ss::quorum_vote_kernel<7, kVoteHoldKB>, grid, 0, stream, a)
+                               : launch(ss::quorum_vote_kernel<7, 0>, grid, 0, stream, a);
     }
 }
 
@@ -684,8 +746,8 @@ int ss_ternary_apply(float *x, const uint32_t *neg, const uint32_t *zero, float 
     Span spans[3] = {span(x, d * sizeof(float), true), span(neg, ss_packed_words(d) * 4, false),
                      span(zero, ss_packed_words(d) * 4, false)};
     if (written_spans_overlap(spans, 3)) return SS_ERR_ARG;
-    constexpr int R = 4;
-    const Tiling t = make_tiling(d, R, false);
+    const bool large = d >= kLargeD && caps_apply();   // then two rows per block, four blocks per unit
+    const Tiling t = make_tiling(d, large ? 2 : 4, false);
     ss::TernaryApplyArgs a;
     a.x = x;
     a.neg = neg;
@@ -695,7 +757,9 @@ int ss_ternary_apply(float *x, const uint32_t *neg, const uint32_t *zero, float 
     a.n_tiles = t.n_tiles;
     const size_t grid = t.n_tiles + t.tail_blocks;
     if (grid > kMaxGrid) return SS_ERR_ARG;
-    return launch(ss::ternary_apply_kernel<R>, grid, 0, static_cast<hipStream_t>(hip_stream), a);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (large) return launch(ss::ternary_apply_kernel<2, 40, true>, grid, 0, stream, a);
+    return launch(ss::ternary_apply_kernel<4, 0, false>, grid, 0, stream, a);
 }
 
 int ss_signum_vote_step_ternary(const void *const *g, ss_dtype gdt, float *const *m, int M, float beta, float tau,
@@ -753,10 +817,17 @@ int ss_stream_copy(void *dst, const void *src, size_t nbytes, void *hip_stream) 
     Span spans[2] = {span(dst, nbytes, true), span(src, nbytes, false)};
     if (written_spans_overlap(spans, 2)) return SS_ERR_ARG;
     const size_t n_vec = nbytes / 16;
-    const size_t grid = (n_vec + ss::kBlock * 4 - 1) / (ss::kBlock * 4);
+    // four blocks of two rows per unit; six of one row from a gigabyte on; without the cap four rows
+    const bool capped = caps_apply();
+    const int rows = !capped ? 4 : (nbytes >= ((size_t)1 << 30) ? 1 : 2);
+    const size_t per_block = (size_t)ss::kBlock * rows;
+    const size_t grid = (n_vec + per_block - 1) / per_block;
     if (grid > kMaxGrid) return SS_ERR_ARG;
     const ss::CopyArgs a{static_cast<ss::f32x4 *>(dst), static_cast<const ss::f32x4 *>(src), n_vec};
-    return launch(ss::copy_kernel, grid, 0, static_cast<hipStream_t>(hip_stream), a);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (rows == 1) return launch(ss::copy_kernel<1, 24>, grid, 0, stream, a);
+    if (rows == 2) return launch(ss::copy_kernel<2, 40>, grid, 0, stream, a);
+    return launch(ss::copy_kernel<4, 0>, grid, 0, stream, a);
 }
 
 }  // extern "C"

@@ -98,6 +98,21 @@ __device__ __forceinline__ uint32_t combine8(uint32_t nibble, int lane) {
     return v;
 }
 
+// Reserves HOLD_KB kilobytes of LDS in the kernel that calls it and never uses them: the only
+// effect is that fewer blocks fit into a compute unit's LDS, i.e. a cap on the traffic a unit
+// keeps in flight (see step_kernels.hpp for why that matters).  `never` must be false at run
+// time; the dead store through `sink` only keeps the compiler from dropping the array.
+template <int HOLD_KB>
+__device__ __forceinline__ void reserve_lds(bool never, uint32_t *sink) {
+    if constexpr (HOLD_KB > 0) {
+        __shared__ uint32_t hold[HOLD_KB * 256];
+        if (never) {
+            hold[threadIdx.x] = threadIdx.x;
+            sink[threadIdx.x] = hold[threadIdx.x ^ 1];
+        }
+    }
+}
+
 // kernel argument block: M device pointers by value (no table in memory)
 template <int N>
 struct PtrTable {

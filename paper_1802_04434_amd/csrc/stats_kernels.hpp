@@ -34,8 +34,9 @@ __device__ __forceinline__ void welford1(float g, float n, float &mean, float &m
     m2 = m2 + p;
 }
 
-template <int R, typename G>
+template <int R, int HOLD_KB, bool LOADS_FIRST, typename G>
 __global__ __launch_bounds__(kBlock) void welford_update_kernel(const WelfordArgs a) {
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0, reinterpret_cast<uint32_t *>(a.mean));
     const int tid = threadIdx.x;
     const size_t tile = blockIdx.x;
     if (tile < a.n_tiles) {
@@ -48,6 +49,7 @@ __global__ __launch_bounds__(kBlock) void welford_update_kernel(const WelfordArg
             mean[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.mean) + q[r]);
             m2[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.m2) + q[r]);
         }
+        if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
 #pragma unroll
@@ -84,8 +86,9 @@ __device__ __forceinline__ float sigma1(float m2, float n) {
     return __builtin_sqrtf(var);
 }
 
-template <int R>
+template <int R, int HOLD_KB, bool LOADS_FIRST>
 __global__ __launch_bounds__(kBlock) void welford_sigma_kernel(const SigmaArgs a) {
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0, reinterpret_cast<uint32_t *>(a.sigma));
     const int tid = threadIdx.x;
     const size_t tile = blockIdx.x;
     if (tile < a.n_tiles) {
@@ -93,6 +96,7 @@ __global__ __launch_bounds__(kBlock) void welford_sigma_kernel(const SigmaArgs a
 #pragma unroll
         for (int r = 0; r < R; ++r)
             v[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.m2) + (tile * R + r) * kBlock + tid);
+        if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             f32x4 s;

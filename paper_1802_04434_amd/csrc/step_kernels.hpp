@@ -137,14 +137,7 @@ __global__ __launch_bounds__(BLOCK) void step_kernel(const StepArgs<NPTR> a) {
     const int M = MT > 0 ? MT : a.M;
     const int T = M / 2 + 1;
     const size_t tile = blockIdx.x;
-    if constexpr (HOLD_KB > 0) {
-        // never true (the host rejects such a d); it only keeps the reservation alive
-        __shared__ uint32_t hold[HOLD_KB * 256];
-        if (a.d == ~(size_t)0) {
-            hold[tid] = (uint32_t)a.M;
-            a.p.packed[0][tid] = hold[tid ^ 1];
-        }
-    }
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0 /* the host rejects such a d */, a.p.packed[0]);
 
     if (tile < a.n_tiles) {
         size_t q[R];

@@ -105,14 +105,7 @@ __global__ __launch_bounds__(BLOCK) void ternary_step_kernel(const TernaryStepAr
     const int lane = tid & 63;
     const int M = a.M;
     const size_t tile = blockIdx.x;
-    if constexpr (HOLD_KB > 0) {
-        // never true (the host rejects such a d); it only keeps the LDS reservation alive
-        __shared__ uint32_t hold[HOLD_KB * 256];
-        if (a.d == ~(size_t)0) {
-            hold[tid] = (uint32_t)a.M;
-            a.voted_neg[tid] = hold[tid ^ 1];
-        }
-    }
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0 /* the host rejects such a d */, VOTE ? a.voted_neg : a.neg_out);
 
     if (tile < a.n_tiles) {
         size_t q[R];
@@ -256,9 +249,11 @@ __device__ __forceinline__ void quorum_batch(const uint32_t *const *neg, const u
     }
 }
 
-// P = number of binary planes of n and z (M < 2^P); t = 2 n + z <= 2 M needs one more
-template <int P>
+// P = number of binary planes of n and z (M < 2^P); t = 2 n + z <= 2 M needs one more.
+// HOLD_KB: LDS reserved to cap the blocks per compute unit.
+template <int P, int HOLD_KB>
 __global__ __launch_bounds__(kBlock) void quorum_vote_kernel(const QuorumVoteArgs a) {
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0, a.voted_neg);
     constexpr int kCountPlanes = P;
     constexpr int kTotalPlanes = P + 1;
     static_assert(kQuorumBatch == 4, "the remainder switch below lists 1 .. 3");
@@ -309,8 +304,9 @@ struct TernaryApplyArgs {
     size_t n_tiles;
 };
 
-template <int R>
+template <int R, int HOLD_KB, bool LOADS_FIRST>
 __global__ __launch_bounds__(kBlock) void ternary_apply_kernel(const TernaryApplyArgs a) {
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0, reinterpret_cast<uint32_t *>(a.x));
     const int tid = threadIdx.x;
     const size_t tile = blockIdx.x;
     if (tile < a.n_tiles) {
@@ -324,6 +320,7 @@ __global__ __launch_bounds__(kBlock) void ternary_apply_kernel(const TernaryAppl
             nw[r] = a.neg[q[r] >> 3];
             zw[r] = a.zero[q[r] >> 3];
         }
+        if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const uint32_t nn = nw[r] >> ((tid & 7) * 4), zn = zw[r] >> ((tid & 7) * 4);

@@ -78,8 +78,9 @@ __device__ __forceinline__ uint32_t live_mask(size_t wi, size_t d) {
     return (1u << (unsigned)(d - lo)) - 1u;
 }
 
-template <int M>
+template <int M, int HOLD_KB>
 __global__ __launch_bounds__(kBlock) void vote_kernel(const VoteArgs<M> a) {
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0, a.voted);
     const size_t u = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (u >= a.n_vec) return;
     u32x4 in[M];
@@ -144,7 +145,9 @@ __device__ __forceinline__ void ripple_all(const uint32_t *const *packed, int M,
     }
 }
 
+template <int HOLD_KB>
 __global__ __launch_bounds__(kBlock) void vote_kernel_any(const VoteArgs<64> a) {
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0, a.voted);
     const size_t u = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (u >= a.n_vec) return;
     const int T = a.M / 2 + 1;
@@ -172,8 +175,11 @@ struct ApplyArgs {
     size_t n_tiles;   // blocks on the vector path, R rows each
 };
 
-template <int R>
+// R rows per block, HOLD_KB of LDS reserved (caps the blocks per compute unit), LOADS_FIRST: every
+// load of the block is issued before the first result is waited for
+template <int R, int HOLD_KB, bool LOADS_FIRST>
 __global__ __launch_bounds__(kBlock) void apply_kernel(const ApplyArgs a) {
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0, reinterpret_cast<uint32_t *>(a.x));
     const int tid = threadIdx.x;
     const size_t tile = blockIdx.x;
     if (tile < a.n_tiles) {
@@ -186,6 +192,7 @@ __global__ __launch_bounds__(kBlock) void apply_kernel(const ApplyArgs a) {
             xv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.x) + q[r]);
             word[r] = a.bits[q[r] >> 3];   // 8 lanes share a word
         }
+        if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const uint32_t nib = word[r] >> ((tid & 7) * 4);
@@ -227,8 +234,9 @@ constexpr int kVoteSumLaneBytes = 128;     // a lane's 128 coordinates give 128 
 constexpr int kVoteSumLdsStride = 144;     // ... kept 144 bytes apart in LDS (spreads the banks)
 
 // P = number of binary planes of the count of "-" votes: counts up to M < 2^P
-template <int P>
+template <int P, int HOLD_KB>
 __global__ __launch_bounds__(kBlock) void vote_sum_kernel(const VoteSumArgs a) {
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0, reinterpret_cast<uint32_t *>(a.sums));   // on top of the tile below
     __shared__ __align__(16) unsigned char tile[kBlock * kVoteSumLdsStride];
     const int tid = threadIdx.x;
     const size_t u = (size_t)blockIdx.x * kBlock + tid;
@@ -291,8 +299,9 @@ struct SumApplyArgs {
     size_t n_tiles;
 };
 
-template <int R>
+template <int R, int HOLD_KB, bool LOADS_FIRST>
 __global__ __launch_bounds__(kBlock) void sum_apply_kernel(const SumApplyArgs a) {
+    reserve_lds<HOLD_KB>(a.d == ~(size_t)0, reinterpret_cast<uint32_t *>(a.x));
     const int tid = threadIdx.x;
     const size_t tile = blockIdx.x;
     if (tile < a.n_tiles) {
@@ -305,6 +314,7 @@ __global__ __launch_bounds__(kBlock) void sum_apply_kernel(const SumApplyArgs a)
             xv[r] = ld_stream(reinterpret_cast<const f32x4 *>(a.x) + q[r]);
             sw[r] = ld_stream(reinterpret_cast<const uint32_t *>(a.sums) + q[r]);
         }
+        if (LOADS_FIRST) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             f32x4 v = xv[r];
@@ -328,14 +338,17 @@ struct CopyArgs {
     size_t n_vec;
 };
 
+template <int R, int HOLD_KB>
 __global__ __launch_bounds__(kBlock) void copy_kernel(const CopyArgs a) {
-    const size_t base = (size_t)blockIdx.x * (kBlock * 4) + threadIdx.x;
-    f32x4 v[4];
+    reserve_lds<HOLD_KB>(a.n_vec == ~(size_t)0, reinterpret_cast<uint32_t *>(a.dst));
+    const size_t base = (size_t)blockIdx.x * (kBlock * R) + threadIdx.x;
+    f32x4 v[R];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < R; ++r)
         if (base + r * kBlock < a.n_vec) v[r] = ld_stream(a.src + base + r * kBlock);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < R; ++r)
         if (base + r * kBlock < a.n_vec) st_stream(a.dst + base + r * kBlock, v[r]);
 }
 
