@@ -193,6 +193,11 @@ int launch_step_m(int M, const void *const *g, float *const *m, uint32_t *const 
             // pack over a large vector: one row per block, six blocks per unit
             if (d >= kLargeD && caps_apply()) return launch_step_shape<1, NPTR, 256, 1, 1, 24, true, true, false, G>(a, d, stream);
         }
+        if constexpr (VOTE) {
+            // the whole step for one worker (Algorithm 1, or Signum on one worker): the same shape from
+            // 2^27 coordinates on (+5-12 % without momentum, +1-8 % with)
+            if (d >= ((size_t)1 << 27) && caps_apply()) return launch_step_shape<1, NPTR, 256, 1, 1, 24, true, HAS_M, true, G>(a, d, stream);
+        }
         constexpr int R = VOTE ? 2 : 4;
         return launch_step_shape<1, NPTR, 256, 1, R, 0, false, HAS_M, VOTE, G>(a, d, stream);
     } else {

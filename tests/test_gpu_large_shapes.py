@@ -65,6 +65,23 @@ def test_pack_large(ss, oracle, dtype):
     assert_same_floats(m_dev, m, "momentum")
 
 
+@pytest.mark.parametrize("momentum", [False, True])
+def test_fused_step_one_worker_large(ss, oracle, momentum):
+    d = D27
+    g = device_normal(d, 13)
+    x_dev = device_normal(d, 14, 0.05)
+    x = synth.as_numpy(x_dev).copy()
+    m_dev = [device_normal(d, 15, 0.3)] if momentum else None
+    m = [synth.as_numpy(m_dev[0]).copy()] if momentum else None
+    voted = dirty_bits(ss, d)
+    ss.signum_vote_step([g], m_dev, 0.9, 1e-4, x_dev, voted, None)
+    want = oracle.signum_vote_step([synth.as_numpy(g)], m, 0.9, 1e-4, x, threads=16)
+    assert np.array_equal(bits_np(voted), want[0] if isinstance(want, tuple) else want)
+    assert_same_floats(x_dev, x, "x")
+    if momentum:
+        assert_same_floats(m_dev[0], m[0], "momentum")
+
+
 def test_pack_ternary_large(ss, oracle):
     d = D28
     g = device_normal(d, 21)
