@@ -122,10 +122,10 @@ int ss_sign_apply(float *x, const uint32_t *bits, float delta, size_t d,
  *   voted       out  ss_packed_bytes(d) bytes: the bits that were applied
  *   packed_out  out  NULL, or host array of M device pointers that receive
  *                    every worker's sign bits (ss_packed_bytes(d) bytes each)
- * Normally one kernel launch.  When packed_out is given, d >= 2^24, the
- * gradients are fp32 and there are 10 workers or more, the call enqueues M + 2
- * launches that hand the signs over through packed_out, which is faster there;
- * the results are the same.  Should the runtime refuse one of those launches
+ * Normally one kernel launch.  When packed_out is given, d >= 2^24 and there
+ * are two workers or more, the call enqueues M + 2 launches that hand the signs
+ * over through packed_out, which is as fast or faster there; the results are
+ * the same.  Should the runtime refuse one of those launches
  * (SS_ERR_HIP), the launches before it stay enqueued: some momentum buffers
  * have then been advanced by this step and x has not.
  */

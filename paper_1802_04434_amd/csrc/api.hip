@@ -111,7 +111,7 @@ constexpr int kLdsPerUnitKB = 160;   // what the reservations below assume; chec
 
 // when ss_signum_vote_step is given packed_out buffers it may run as M + 2 launches (see there)
 constexpr size_t kSplitMinD = (size_t)1 << 24;
-constexpr int kSplitMinWorkers = 10;
+constexpr int kSplitMinWorkers = 2;
 
 // LDS of one compute unit of the current device, in KB; 0 if the runtime will not say.  A pure
 // query: nothing is remembered between calls.
@@ -449,13 +449,12 @@ int ss_signum_vote_step_ex(const void *const *g, ss_dtype gdt, float *const *m, 
         spans[n++] = span(sums_out, d, true);
         if (written_spans_overlap(spans, n)) return SS_ERR_ARG;
     }
-    // Many workers with fp32 gradients over a large vector, and the caller wants every worker's
-    // bits anyway: then those buffers can carry the signs from launch to launch, and M pack
-    // launches + vote + apply (each touching three streams chip-wide at a time) measured 5 %
-    // faster at M = 16 than the one-pass kernel with its 2M+1 input and M+1 output streams.  Same
-    // results, bit for bit.  (With bf16 gradients the one-pass kernel is the faster one.)
-    if (packed_out && !sums_out && !(flags & SS_STEP_SUM_UPDATE) && d >= kSplitMinD && gdt == SS_F32 &&
-        M >= kSplitMinWorkers) {
+    // A large vector, and the caller wants every worker's bits anyway: then those buffers can carry
+    // the signs from launch to launch, and M pack launches + vote + apply (each touching two or
+    // three buffers chip-wide at a time) are never slower than the one-pass kernel that also writes
+    // the bits, and up to 10 % faster (measured for M = 2 .. 16 at 2^25, 1.4 * 2^27 and 2^29
+    // coordinates: fp32 0-8 %, bf16 2-10 %).  Same results, bit for bit.
+    if (packed_out && !sums_out && !(flags & SS_STEP_SUM_UPDATE) && d >= kSplitMinD && M >= kSplitMinWorkers) {
         for (int w = 0; w < M; ++w) {
             const int rc = signum_pack_impl(g[w], gdt, m ? m[w] : nullptr, beta, packed_out[w], d,
                                             flags & SS_STEP_WARMUP, hip_stream);
